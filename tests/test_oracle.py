@@ -1,0 +1,407 @@
+"""Pins for the CPU oracle (no GPU): hand-worked cases, closed forms, brute force, invariants, and
+special cases that reduce to a library routine.  Each pin is chosen so that a plausible mistake in
+the oracle (wrong mask edge, transposed operand, dropped segment, wrong tie rule) fails it."""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import scipy.special
+
+import oracle
+from paper_2601_21444_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def bits(x, shape=None):
+    a = wl.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))
+    return a.reshape(shape) if shape is not None else a
+
+
+def as_thd(rows, d=2):
+    """list of d-vectors -> [tokens, 1, d] bf16 bits."""
+    a = np.asarray(rows, dtype=np.float32).reshape(-1, 1, d)
+    return bits(a)
+
+
+def rand_bits(rng, shape, scale=1.0):
+    return bits(rng.standard_normal(shape).astype(np.float32) * np.float32(scale))
+
+
+# ------------------------------------------------------------------ independent brute force (pure Python)
+
+def brute_attention(q, ka, va, kp, vp, k, v, scale):
+    """Eq. 1 over the concatenated KV of Eq. 4, scalar loops, math.exp/fsum; inputs are float lists
+    [tokens][heads][d]."""
+    L, hq, d = len(q), len(q[0]), len(q[0][0])
+    hkv = len(k[0])
+    g = hq // hkv
+    out = [[[0.0] * d for _ in range(hq)] for _ in range(L)]
+    lse = [[0.0] * L for _ in range(hq)]
+    for i in range(L):
+        for h in range(hq):
+            kv = h // g
+            keys = [r[kv] for r in ka] + [r[kv] for r in kp] + [k[j][kv] for j in range(i + 1)]
+            vals = [r[kv] for r in va] + [r[kv] for r in vp] + [v[j][kv] for j in range(i + 1)]
+            logits = [scale * math.fsum(q[i][h][c] * kk[c] for c in range(d)) for kk in keys]
+            m = max(logits)
+            w = [math.exp(z - m) for z in logits]
+            den = math.fsum(w)
+            for c in range(d):
+                out[i][h][c] = math.fsum(wj * vj[c] for wj, vj in zip(w, vals)) / den
+            lse[h][i] = m + math.log(den)
+    return np.array(out), np.array(lse)
+
+
+def to_lists(b):
+    return wl.bf16_bits_to_f32(b).astype(np.float64).tolist()
+
+
+# ------------------------------------------------------------------ attention pins
+
+with open(os.path.join(GOLDEN, "handworked_attention.json")) as f:
+    HAND_ATT = json.load(f)["cases"]
+
+
+@pytest.mark.parametrize("case", HAND_ATT, ids=[c["name"] for c in HAND_ATT])
+def test_attention_handworked(case):
+    args = [as_thd(case[n]) for n in ("q", "k_anchor", "v_anchor", "k_pass", "v_pass", "k", "v")]
+    out, lse = oracle.host_attention(*args, scale=math.log(2.0))
+    exp = np.array(case["out_num"], dtype=np.float64) / np.array(case["out_den"], dtype=np.float64)[:, None]
+    np.testing.assert_allclose(out[:, 0, :], exp, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(lse[0], np.log(np.array(case["out_den"], dtype=np.float64)), rtol=0, atol=1e-14)
+
+
+def test_attention_uniform_logits_is_running_mean():
+    """All keys identical => softmax is uniform over the visible set => row i is the mean of the
+    anchor, passing and first i+1 local value rows (closed form; catches any mask off-by-one)."""
+    rng = np.random.default_rng(5)
+    l_a, n_p, L, d = 5, 7, 33, 8
+    kconst = rng.standard_normal(d).astype(np.float32)
+    mk = lambda n: bits(np.broadcast_to(kconst, (n, 1, d)).copy())
+    va, vp, v = (rand_bits(rng, (n, 1, d)) for n in (l_a, n_p, L))
+    q = rand_bits(rng, (L, 2, d))
+    out, lse = oracle.host_attention(q, mk(l_a), va, mk(n_p), vp, mk(L), v, scale=0.3)
+    vv = np.concatenate([oracle.bf16_bits_to_f64(x)[:, 0] for x in (va, vp, v)])
+    for i in range(L):
+        exp = vv[: l_a + n_p + i + 1].mean(axis=0)
+        np.testing.assert_allclose(out[i, 0], exp, atol=1e-13)
+        np.testing.assert_allclose(out[i, 1], exp, atol=1e-13)
+    # lse = logit + log(count)
+    qf = oracle.bf16_bits_to_f64(q)
+    kf = oracle.bf16_bits_to_f64(mk(1))[0, 0]
+    for i in (0, 1, L - 1):
+        z = 0.3 * float(qf[i, 1] @ kf)
+        assert lse[1, i] == pytest.approx(z + math.log(l_a + n_p + i + 1), abs=1e-12)
+
+
+@pytest.mark.parametrize("hq,hkv,d,l_a,n_p,L", [(1, 1, 2, 0, 0, 6), (4, 2, 4, 3, 5, 9), (3, 1, 8, 0, 4, 7), (2, 2, 4, 6, 0, 5)])
+def test_attention_matches_pure_python_bruteforce(hq, hkv, d, l_a, n_p, L):
+    rng = np.random.default_rng(100 + L)
+    q = rand_bits(rng, (L, hq, d))
+    ka, va, kp, vp, k, v = (rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_p, n_p, L, L))
+    scale = 1.0 / math.sqrt(d)
+    out, lse = oracle.host_attention(q, ka, va, kp, vp, k, v, scale)
+    bo, bl = brute_attention(*(to_lists(x) for x in (q, ka, va, kp, vp, k, v)), scale)
+    np.testing.assert_allclose(out, bo, atol=1e-13)
+    np.testing.assert_allclose(lse, bl, atol=1e-13)
+
+
+def test_attention_degenerates_to_causal_softmax_library():
+    """No anchor, no passing block: plain causal attention (the single-GPU degenerate case named in
+    the Limitations section).  Compare with scipy's softmax applied to a lower-triangular logit matrix."""
+    rng = np.random.default_rng(7)
+    L, hq, hkv, d = 70, 4, 2, 16
+    q, k, v = rand_bits(rng, (L, hq, d)), rand_bits(rng, (L, hkv, d)), rand_bits(rng, (L, hkv, d))
+    e = np.empty((0, hkv, d), dtype=np.uint16)
+    scale = 1.0 / math.sqrt(d)
+    out, lse = oracle.host_attention(q, e, e, e, e, k, v, scale, chunk=32)
+    qf, kf, vf = (wl.bf16_bits_to_f32(x).astype(np.float64) for x in (q, k, v))
+    for h in range(hq):
+        z = scale * qf[:, h] @ kf[:, h // 2].T
+        z = np.where(np.tril(np.ones((L, L), dtype=bool)), z, -np.inf)
+        p = scipy.special.softmax(z, axis=1)
+        np.testing.assert_allclose(out[:, h], p @ vf[:, h // 2], atol=1e-13)
+        np.testing.assert_allclose(lse[h], scipy.special.logsumexp(z, axis=1), atol=1e-12)
+
+
+def test_uncompressed_passing_equals_dense_attention():
+    """l_p = block length ("no compression"): every passing block is a permutation of the full
+    preceding block, so the result must equal dense attention over [anchor | preceding blocks in
+    natural order | local causal]."""
+    cfg = wl.custom("nocomp", 11, 4, 2, 16, 5, 12, 3, 40, 40, 48)
+    x = wl.generate(cfg)
+    k_p, v_p = oracle.make_passing_block(x.q_probe, x.k_prev, x.v_prev, cfg.l_p, cfg.n_kv_heads, cfg.head_dim)
+    assert k_p.shape == (cfg.P * cfg.L_prev, cfg.n_kv_heads, cfg.head_dim)
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    out, lse = oracle.host_attention(x.q, x.k_anchor, x.v_anchor, k_p, v_p, x.k, x.v, scale)
+    # dense reference with an independent softmax routine
+    f = lambda b: wl.bf16_bits_to_f32(b).astype(np.float64)
+    kd = np.concatenate([f(x.k_anchor)] + [f(a) for a in x.k_prev] + [f(x.k)])
+    vd = np.concatenate([f(x.v_anchor)] + [f(a) for a in x.v_prev] + [f(x.v)])
+    n_vis = cfg.l_a + cfg.P * cfg.L_prev
+    vis = np.ones((cfg.L, n_vis + cfg.L), dtype=bool)
+    vis[:, n_vis:] = np.tril(np.ones((cfg.L, cfg.L), dtype=bool))
+    for h in range(cfg.n_q_heads):
+        z = scale * f(x.q)[:, h] @ kd[:, h // cfg.group].T
+        p = scipy.special.softmax(np.where(vis, z, -np.inf), axis=1)
+        np.testing.assert_allclose(out[:, h], p @ vd[:, h // cfg.group], atol=1e-12)
+    # and the compressed version must differ (the test would be vacuous otherwise)
+    k_c, v_c = oracle.make_passing_block(x.q_probe, x.k_prev, x.v_prev, 8, cfg.n_kv_heads, cfg.head_dim)
+    out_c, _ = oracle.host_attention(x.q, x.k_anchor, x.v_anchor, k_c, v_c, x.k, x.v, scale)
+    assert np.abs(out_c - out).max() > 1e-3
+
+
+def test_passing_segment_is_permutation_invariant_and_anchor_passing_interchangeable():
+    rng = np.random.default_rng(3)
+    hq, hkv, d, l_a, n_p, L = 2, 1, 8, 6, 10, 12
+    q = rand_bits(rng, (L, hq, d))
+    ka, va, kp, vp, k, v = (rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_p, n_p, L, L))
+    o0, l0 = oracle.host_attention(q, ka, va, kp, vp, k, v, 0.35)
+    perm = rng.permutation(n_p)
+    o1, l1 = oracle.host_attention(q, ka, va, kp[perm], vp[perm], k, v, 0.35)
+    np.testing.assert_allclose(o1, o0, atol=1e-13)
+    np.testing.assert_allclose(l1, l0, atol=1e-13)
+    # moving all anchor keys into the passing segment changes nothing (both are fully visible)
+    e = np.empty((0, hkv, d), dtype=np.uint16)
+    o2, _ = oracle.host_attention(q, e, e, np.concatenate([ka, kp]), np.concatenate([va, vp]), k, v, 0.35)
+    np.testing.assert_allclose(o2, o0, atol=1e-13)
+    # but swapping K and V operands, or local<->passing, does change it
+    o3, _ = oracle.host_attention(q, ka, va, k[:n_p], v[:n_p], np.concatenate([kp, k[n_p:]]), np.concatenate([vp, v[n_p:]]), 0.35)
+    assert np.abs(o3 - o0).max() > 1e-3
+
+
+def needle_key(qrow, d):
+    """A key whose logit with qrow is huge: 8 * q/|q| * sqrt(d) (before bf16 rounding)."""
+    return 8.0 * qrow / np.linalg.norm(qrow) * math.sqrt(d)
+
+
+def test_mask_needles():
+    """A key with an overwhelming logit: invisible when planted at a masked position, and the whole
+    output when planted at each boundary-visible position."""
+    rng = np.random.default_rng(21)
+    hq, hkv, d, l_a, n_p, L = 1, 1, 16, 4, 6, 10
+    q = rand_bits(rng, (L, hq, d))
+    base = [rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_p, n_p, L, L)]
+    scale = 1.0  # logit of the needle ~ 8*|q|*sqrt(d) ~ 128: weight of all others < e^-100
+    qf = oracle.bf16_bits_to_f64(q)
+    o_base, _ = oracle.host_attention(q, *base, scale)
+    i = 4
+
+    def run(seg, pos):
+        t = [a.copy() for a in base]
+        kseg = {"a": 0, "p": 2, "l": 4}[seg]
+        t[kseg][pos, 0] = bits(needle_key(qf[i, 0], d).astype(np.float32))
+        o, _ = oracle.host_attention(q, *t, scale)
+        return o, oracle.bf16_bits_to_f64(t[kseg + 1])[pos, 0]
+
+    # masked: local key i+1 (and the last local key) must not move row i
+    for pos in (i + 1, L - 1):
+        o, _ = run("l", pos)
+        np.testing.assert_allclose(o[i], o_base[i], atol=1e-13)
+    # visible boundaries: diagonal, first local key, last anchor key, first/last passing key
+    for seg, pos in (("l", i), ("l", 0), ("a", l_a - 1), ("a", 0), ("p", 0), ("p", n_p - 1)):
+        o, vrow = run(seg, pos)
+        np.testing.assert_allclose(o[i, 0], vrow, atol=1e-9)
+
+
+def test_attention_invariants_and_row_subset():
+    cfg = wl.custom("inv", 2, 4, 2, 8, 4, 7, 2, 30, 5, 41)
+    x = wl.generate(cfg)
+    k_p, v_p = oracle.make_passing_block(x.q_probe, x.k_prev, x.v_prev, cfg.l_p, cfg.n_kv_heads, cfg.head_dim)
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+    out, lse = oracle.host_attention(x.q, x.k_anchor, x.v_anchor, k_p, v_p, x.k, x.v, scale, chunk=16)
+    vf = np.concatenate([oracle.bf16_bits_to_f64(a) for a in (x.v_anchor, v_p, x.v)])
+    kf = np.concatenate([oracle.bf16_bits_to_f64(a) for a in (x.k_anchor, k_p, x.k)])
+    qf = oracle.bf16_bits_to_f64(x.q)
+    n_vis = cfg.l_a + cfg.P * cfg.l_p
+    for h in range(cfg.n_q_heads):
+        kv = h // cfg.group
+        for i in (0, 13, cfg.L - 1):
+            vis = vf[: n_vis + i + 1, kv]
+            assert np.all(out[i, h] <= vis.max(axis=0) + 1e-12) and np.all(out[i, h] >= vis.min(axis=0) - 1e-12)
+            z = scale * kf[: n_vis + i + 1, kv] @ qf[i, h]
+            assert lse[h, i] >= z.max()
+            assert lse[h, i] == pytest.approx(math.log(math.fsum(math.exp(t) for t in z)), abs=1e-12)
+    rows = np.array([40, 0, 17])
+    o2, l2 = oracle.host_attention(x.q, x.k_anchor, x.v_anchor, k_p, v_p, x.k, x.v, scale, rows=rows)
+    np.testing.assert_array_equal(o2, out[rows])
+    np.testing.assert_array_equal(l2, lse[:, rows])
+
+
+def test_visibility_mask_counts_match_closed_forms():
+    """Visible-pair count L*(l_a+P*l_p) + L(L+1)/2, and the per-physical-host FLOP formula of
+    App. B.2, 2*l_a^2*d + 4*l_b^2*d + 4(2H-1)*l_p*l_b*d, once the terms it leaves out are restored."""
+    l_a, l_p, L, d, H = 6, 3, 11, 4, 4
+    tot = 0
+    for h in range(2 * H):
+        m = oracle.visibility_mask(np.arange(L), l_a, h * l_p, L)
+        cfg = wl.custom("x", 0, 1, 1, d, 1, l_a, h, L, l_p, L)
+        assert int(m.sum()) == cfg.visible_pairs_per_head
+        assert cfg.attention_flops == 4 * d * int(m.sum())
+        tot += int(m.sum())
+    # physical host h holds virtual hosts h and 2H-1-h: the sum is h-independent
+    per_phys = [oracle.visibility_mask(np.arange(L), l_a, h * l_p, L).sum()
+                + oracle.visibility_mask(np.arange(L), l_a, (2 * H - 1 - h) * l_p, L).sum() for h in range(H)]
+    assert len(set(int(p) for p in per_phys)) == 1
+    paper = 2 * l_a * l_a * d + 4 * L * L * d + 4 * (2 * H - 1) * l_p * L * d
+    # the formula counts the anchor's own causal attention (2*l_a^2*d), counts a causal block as
+    # exactly half (L^2/2 instead of L(L+1)/2) and omits context->anchor attention (4*l_a*L*d per block)
+    ours = 4 * d * int(per_phys[0])
+    assert ours == paper - 2 * l_a * l_a * d + 8 * l_a * L * d + 4 * L * d
+
+
+# ------------------------------------------------------------------ scoring pins
+
+def frac(bits_arr):
+    """bf16 bit patterns -> exact Fractions."""
+    return [Fraction(float(x)) for x in wl.bf16_bits_to_f32(np.asarray(bits_arr).ravel()).tolist()]
+
+
+def test_scores_exact_rational_tiny():
+    """Exact evaluation of sum_t sum_g q[t, vG+g] . k[j, v] in rational arithmetic."""
+    rng = np.random.default_rng(8)
+    n_q, hq, hkv, d, L = 3, 4, 2, 4, 9
+    qp, k = rand_bits(rng, (n_q, hq, d)), rand_bits(rng, (L, hkv, d))
+    s = oracle.importance_scores(qp, k)
+    qfr = np.array(frac(qp), dtype=object).reshape(n_q, hq, d)
+    kfr = np.array(frac(k), dtype=object).reshape(L, hkv, d)
+    g = hq // hkv
+    for v in range(hkv):
+        for j in range(L):
+            exact = sum(qfr[t, v * g + gg, c] * kfr[j, v, c] for t in range(n_q) for gg in range(g) for c in range(d))
+            assert abs(Fraction(float(s[v, j])) - exact) <= abs(exact) * Fraction(1, 10**15) + Fraction(1, 10**18)
+
+
+def test_scores_equal_sum_of_explicit_logit_matrix():
+    """Linearity: the pooled-query dot product equals the n_q*G x L logit matrix of Alg. 1 summed over
+    its rows (computed the long way with a library matmul)."""
+    rng = np.random.default_rng(9)
+    n_q, hq, hkv, d, L = 16, 6, 2, 32, 300
+    qp, k = rand_bits(rng, (n_q, hq, d)), rand_bits(rng, (L, hkv, d))
+    s = oracle.importance_scores(qp, k)
+    qf, kf = wl.bf16_bits_to_f32(qp).astype(np.float64), wl.bf16_bits_to_f32(k).astype(np.float64)
+    g = hq // hkv
+    for v in range(hkv):
+        S = np.concatenate([qf[:, v * g + gg, :] @ kf[:, v, :].T for gg in range(g)], axis=0)   # [n_q*G, L]
+        np.testing.assert_allclose(s[v], S.sum(axis=0), rtol=1e-12, atol=1e-11)
+    # head grouping matters: a wrong group mapping gives different scores
+    S_wrong = sum(qf[:, gg, :] @ kf[:, 1, :].T for gg in range(g)).sum(axis=0)
+    assert np.abs(S_wrong - s[1]).max() > 1e-3
+
+
+def test_identical_key_rows_get_identical_scores():
+    rng = np.random.default_rng(10)
+    qp, k = rand_bits(rng, (8, 2, 64)), rand_bits(rng, (257, 1, 64))
+    k[200] = k[3]
+    k[256] = k[3]
+    s = oracle.importance_scores(qp, k)
+    assert s[0, 200] == s[0, 3] == s[0, 256]
+
+
+# ------------------------------------------------------------------ ArgTop / gather pins
+
+with open(os.path.join(GOLDEN, "handworked_argtop.json")) as f:
+    HAND_TOP = json.load(f)["cases"]
+
+
+@pytest.mark.parametrize("case", HAND_TOP)
+def test_argtop_handworked(case):
+    got = oracle.arg_top(np.array(case["scores"], dtype=np.float64), case["l_p"])
+    assert got.dtype == np.int32
+    assert got.tolist() == case["idx"]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_argtop_bruteforce_with_ties(seed):
+    rng = np.random.default_rng(seed)
+    L = 200
+    s = rng.integers(-5, 6, size=L).astype(np.float64) * 0.25      # many exact ties
+    for l_p in (0, 1, 17, 199, 200):
+        got = oracle.arg_top(s, l_p).tolist()
+        exp = sorted(range(L), key=lambda j: (-s[j], j))[:l_p]
+        assert got == exp
+        assert len(set(got)) == l_p
+        if 0 < l_p < L:
+            rest = sorted(set(range(L)) - set(got))
+            assert min(s[got]) >= max(s[rest])
+
+
+def test_argtop_rejects_bad_arguments():
+    with pytest.raises(ValueError):
+        oracle.arg_top(np.zeros(4), 5)
+    with pytest.raises(ValueError):
+        oracle.arg_top(np.array([0.0, np.nan]), 1)
+
+
+def test_compress_gathers_bit_copies_per_head():
+    cfg = wl.custom("c", 4, 4, 2, 16, 6, 0, 0, 0, 13, 90)
+    x = wl.generate(cfg)
+    x.k[50] = x.k[7]                                     # planted exact tie (both heads)
+    idx, k_c, v_c, s = oracle.compress_kv(x.q_probe, x.k, x.v, cfg.l_p)
+    assert idx.shape == (2, 13) and k_c.shape == (13, 2, 16) and k_c.dtype == np.uint16
+    for h in range(2):
+        exp = sorted(range(cfg.L), key=lambda j: (-s[h, j], j))[:13]
+        assert idx[h].tolist() == exp
+        np.testing.assert_array_equal(k_c[:, h], x.k[idx[h], h])
+        np.testing.assert_array_equal(v_c[:, h], x.v[idx[h], h])
+    assert not np.array_equal(idx[0], idx[1])            # heads select independently
+    # l_p = L is a permutation, l_p = 0 is empty
+    idx_all, k_all, _, _ = oracle.compress_kv(x.q_probe, x.k, x.v, cfg.L)
+    assert sorted(idx_all[0].tolist()) == list(range(cfg.L))
+    pos7, pos50 = idx_all[0].tolist().index(7), idx_all[0].tolist().index(50)
+    assert pos50 == pos7 + 1                             # tie -> lower index first, adjacent
+    idx0, k0, v0, _ = oracle.compress_kv(x.q_probe, x.k, x.v, 0)
+    assert idx0.shape == (2, 0) and k0.shape == (0, 2, 16)
+
+
+def test_passing_block_is_host_ordered_concatenation():
+    cfg = wl.custom("p", 6, 2, 1, 8, 4, 3, 3, 20, 4, 10)
+    x = wl.generate(cfg)
+    k_p, v_p = oracle.make_passing_block(x.q_probe, x.k_prev, x.v_prev, cfg.l_p, 1, 8)
+    assert k_p.shape == (12, 1, 8)
+    for p in range(3):
+        _, k_c, v_c, _ = oracle.compress_kv(x.q_probe, x.k_prev[p], x.v_prev[p], 4)
+        np.testing.assert_array_equal(k_p[4 * p: 4 * p + 4], k_c)
+        np.testing.assert_array_equal(v_p[4 * p: 4 * p + 4], v_c)
+    k0, v0 = oracle.make_passing_block(x.q_probe, [], [], 4, 1, 8)
+    assert k0.shape == (0, 1, 8)
+
+
+# ------------------------------------------------------------------ input generator
+
+def test_bf16_rounding_and_widening():
+    x = np.array([1.0, 1.00390625, 1.01171875, -2.5, 0.0, 3.140625, 1e-3], dtype=np.float32)
+    b = wl.f32_to_bf16_bits(x)
+    back = wl.bf16_bits_to_f32(b)
+    # 1 + 2^-8 is a tie between 1 and 1 + 2^-7 -> even (1.0); 1 + 3*2^-8 ties to 1 + 2^-6 (even mantissa)
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == np.float32(1.015625)
+    assert back[3] == -2.5 and back[4] == 0.0 and back[5] == np.float32(3.140625)
+    assert abs(back[6] - 1e-3) <= 1e-3 * 2 ** -8
+    np.testing.assert_array_equal(oracle.bf16_bits_to_f64(b), back.astype(np.float64))
+    try:
+        import torch
+        t = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        np.testing.assert_array_equal(b, t)
+    except ImportError:  # pragma: no cover
+        pass
+
+
+def test_generator_is_seeded_and_shaped():
+    a, b = wl.generate("tiny"), wl.generate("tiny")
+    cfg = a.cfg
+    np.testing.assert_array_equal(a.k, b.k)
+    assert a.q_probe.shape == (8, 2, 64) and a.q.shape == (512, 2, 64)
+    assert a.k_anchor.shape == (64, 1, 64) and len(a.k_prev) == 3 and a.k_prev[0].shape == (512, 1, 64)
+    assert cfg.s_kv == 672 and cfg.visible_pairs_per_head == 213248
+    big = wl.CONFIGS["3b-128k"]
+    assert big.s_kv == 25600 and big.visible_pairs_per_head == 285220864
+    assert big.attention_flops == 2336529317888 and big.compress_bytes == 8388608 + 2097152 + 8192
+    fr = wl.custom("f", 3, 2, 2, 128, 4, 0, 0, 0, 8, 8192, key_recipe="frames")
+    kf = wl.bf16_bits_to_f32(wl.generate(fr).k)
+    # frame structure: within-frame mean is far from zero, tokens scatter around it with std ~0.5
+    mu = kf[:4096].mean(axis=0)
+    assert 0.5 < mu.std() < 2.0 and 0.4 < (kf[:4096] - mu).std() < 0.6
