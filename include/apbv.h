@@ -1,0 +1,123 @@
+/*
+ * apbv.h -- C ABI of the MI355X (gfx950) library for one virtual host's share of APB-V's approximate
+ * prefill attention (arXiv 2601.21444).
+ *
+ * Two operations make up the per-layer hot path of a host (Alg. 1):
+ *   apbv_compress_kv     Sec. 3.3 / Alg. 1 "Identify Essential KVs" + "Send Block's Essential KVs":
+ *                        score every local key against the query block, keep the l_p best per KV head,
+ *                        gather them into the compressed block (K_c, V_c).
+ *   apbv_host_attention  Eq. 4 (with Eq. 1): attention of the local query block over the concatenation
+ *                        [anchor | passing | local], anchor and passing fully visible, local causal.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer (HIP global memory on the current device) unless a
+ *     parameter is explicitly marked host.  bf16 values are passed as their 16-bit patterns.
+ *   - The caller owns every buffer (inputs, outputs, workspace).  The library allocates no device
+ *     memory and keeps no state between calls.
+ *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and outputs are valid once the caller has synchronised that stream.
+ *   - Inputs are never written.  Outputs and workspace must not overlap inputs or each other.
+ *   - Every argument error is detected on the host before anything is launched and reported through
+ *     the return value; nothing is launched in that case.  No function throws or aborts.
+ *   - Inputs must be finite; NaN/Inf give an unspecified ranking / output.
+ *   - `batch` = independent problems of identical shape (for instance the two virtual hosts of one
+ *     physical host, Sec. 4.3, or concurrent requests).
+ */
+#ifndef APBV_H_
+#define APBV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  APBV_OK = 0,
+  APBV_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  APBV_ERR_SHAPE = -2,       /* inconsistent or out-of-range sizes / strides                 */
+  APBV_ERR_UNSUPPORTED = -3, /* head_dim or size outside what the kernels implement          */
+  APBV_ERR_WORKSPACE = -4,   /* workspace NULL, misaligned or too small                      */
+  APBV_ERR_LAUNCH = -5       /* the HIP runtime refused a launch (hipGetLastError != success)*/
+} apbv_status;
+
+/* A [tokens, heads, head_dim] bf16 view.  head_dim is contiguous (stride 1); all strides are in
+ * ELEMENTS and must be multiples of 8 (16-byte vector access); ptr must be 16-byte aligned.
+ * ptr may be NULL iff tokens == 0.  stride_batch is ignored when batch == 1. */
+typedef struct {
+  const void* ptr;
+  int64_t tokens;
+  int64_t stride_token;
+  int64_t stride_head;
+  int64_t stride_batch;
+} apbv_tensor;
+
+/* Host, pure.  Static string naming a status code. */
+const char* apbv_status_string(apbv_status s);
+
+/* Host, pure.  Library version, major*10000 + minor*100 + patch. */
+int apbv_version(void);
+
+/* Host, pure.  Bytes of workspace apbv_compress_kv needs for this shape (0 on invalid arguments).
+ * The workspace must be 256-byte aligned.  Its contents need no initialisation and are garbage
+ * afterwards. */
+size_t apbv_compress_workspace_bytes(int batch, int n_kv_heads, int head_dim, int64_t L, int64_t l_p);
+
+/*
+ * KV compression of one context block (Sec. 3.3; Alg. 1: S_h <- Q_qr K^(h)T, then
+ * (K^(h), V^(h)).gather(ArgTop_{l_p}(S_h))).
+ *
+ * For every batch item b and KV head v (G = n_q_heads / n_kv_heads):
+ *   s[j]   = sum_{t < n_q} sum_{g < G} Q_qr[t, v*G+g, :] . K[j, v, :]     (float64 accumulation)
+ *   idx    = the l_p indices j with the largest s[j], ordered by descending s; equal scores
+ *            (compared as real numbers) by ascending j
+ *   K_c[i, v, :] = K[idx[i], v, :],   V_c[i, v, :] = V[idx[i], v, :]      (bit copies)
+ *
+ *   q_probe   Q_qr  [n_q, Hq,  d], n_q = q_probe.tokens >= 1
+ *   k_local   K^(h) [L,   Hkv, d], L = k_local.tokens >= 1
+ *   v_local   V^(h) [L,   Hkv, d], same token count
+ *   l_p       0 <= l_p <= L   (l_p == 0: nothing is written to idx/k_c/v_c, which may then be NULL)
+ *   idx_out   [batch, Hkv, l_p] int32
+ *   k_c_out, v_c_out   [batch, l_p, Hkv, d] bf16, dense
+ *   scores_out  optional (may be NULL): [batch, Hkv, L] float64, the ranking scores s
+ *   workspace / workspace_bytes   at least apbv_compress_workspace_bytes(...) bytes, 256-byte aligned
+ *
+ * Supported: head_dim in {64, 128}; L <= 2^24; n_q_heads % n_kv_heads == 0.
+ */
+apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                             apbv_tensor q_probe, apbv_tensor k_local, apbv_tensor v_local,
+                             int64_t l_p,
+                             int32_t* idx_out, void* k_c_out, void* v_c_out, double* scores_out,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Fused host attention (Eq. 4 by the definition of Eq. 1):
+ *   O[i, h, :] = sum_j softmax_j( softmax_scale * Q[i, h, :] . Kcat[j, h/G, :] + mask(i, j) ) Vcat[j, h/G, :]
+ * over Kcat = [K_a ; K_p ; K], Vcat = [V_a ; V_p ; V]; mask = 0 for anchor and passing keys; local key
+ * j' is visible to local query i iff j' <= i (so every row sees at least one key).
+ *
+ *   q_local              Q^(h) [L, Hq, d]
+ *   k_anchor, v_anchor   [l_a,   Hkv, d]   l_a  >= 0
+ *   k_pass,   v_pass     [n_p,   Hkv, d]   n_p = P*l_p >= 0, blocks of the preceding hosts in host order
+ *   k_local,  v_local    [L,     Hkv, d]   L >= 1; row i of q_local is the query of local key i
+ *   softmax_scale        the paper's 1/sqrt(head_dim); any finite positive value is accepted
+ *   out                  [batch, L, Hq, d] bf16, dense
+ *   lse_out              optional (may be NULL): [batch, Hq, L] float32, natural-log sum of the
+ *                        exponentials of the scaled visible logits (for merging partial results)
+ *
+ * Arithmetic: bf16 operands, fp32 accumulation and softmax, probabilities rounded to bf16 before the
+ * PV product, output rounded to bf16.
+ * Supported: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0; each K/V pair must agree in tokens.
+ */
+apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                                apbv_tensor q_local,
+                                apbv_tensor k_anchor, apbv_tensor v_anchor,
+                                apbv_tensor k_pass, apbv_tensor v_pass,
+                                apbv_tensor k_local, apbv_tensor v_local,
+                                float softmax_scale, void* out, float* lse_out, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APBV_H_ */

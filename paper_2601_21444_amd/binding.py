@@ -1,0 +1,174 @@
+"""Thin ctypes binding of libapbv.so: argument marshalling only.
+
+Every step of the hot path runs inside the HIP library; PyTorch is used here for device memory and
+for the current HIP stream.  If the library has not been built the calls raise -- there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libapbv.so")
+_lib = None
+
+
+class ApbvError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {status_string(code)} ({code})")
+        self.code = code
+
+
+class ApbvTensor(ctypes.Structure):
+    """Mirror of ``apbv_tensor`` in include/apbv.h."""
+    _fields_ = [
+        ("ptr", ctypes.c_void_p),
+        ("tokens", ctypes.c_int64),
+        ("stride_token", ctypes.c_int64),
+        ("stride_head", ctypes.c_int64),
+        ("stride_batch", ctypes.c_int64),
+    ]
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libapbv.so (built in-tree by ``paper_2601_21444_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build the HIP library first (python -m paper_2601_21444_amd.build). "
+            "There is no CPU or PyTorch fallback for the APB-V hot path.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    lib.apbv_status_string.restype = ctypes.c_char_p
+    lib.apbv_status_string.argtypes = [ctypes.c_int]
+    lib.apbv_version.restype = ctypes.c_int
+    lib.apbv_version.argtypes = []
+    lib.apbv_compress_workspace_bytes.restype = ctypes.c_size_t
+    lib.apbv_compress_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64]
+    lib.apbv_compress_kv.restype = ctypes.c_int
+    lib.apbv_compress_kv.argtypes = [
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ApbvTensor, ApbvTensor, ApbvTensor, ctypes.c_int64,
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.apbv_host_attention.restype = ctypes.c_int
+    lib.apbv_host_attention.argtypes = [
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor,
+        ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    _lib = lib
+    return lib
+
+
+def status_string(code: int) -> str:
+    return load_library().apbv_status_string(int(code)).decode()
+
+
+def apbv_version() -> int:
+    return int(load_library().apbv_version())
+
+
+def apbv_compress_workspace_bytes(batch: int, n_kv_heads: int, head_dim: int, L: int, l_p: int) -> int:
+    return int(load_library().apbv_compress_workspace_bytes(batch, n_kv_heads, head_dim, L, l_p))
+
+
+def tensor_view(t: torch.Tensor) -> Tuple[ApbvTensor, int]:
+    """``[tokens, heads, d]`` or ``[batch, tokens, heads, d]`` bf16 tensor -> (apbv_tensor, batch)."""
+    if t.dtype != torch.bfloat16:
+        raise TypeError("expected a bfloat16 tensor")
+    if t.dim() == 3:
+        t = t.unsqueeze(0)
+    if t.dim() != 4:
+        raise ValueError("expected [tokens, heads, d] or [batch, tokens, heads, d]")
+    if t.shape[1] > 0 and t.stride(3) != 1:
+        raise ValueError("head_dim must be contiguous")
+    b, n, _, _ = t.shape
+    view = ApbvTensor(t.data_ptr() if n > 0 else None, n, t.stride(1), t.stride(2), t.stride(0))
+    return view, b
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def apbv_compress_kv(q_probe: torch.Tensor, k_local: torch.Tensor, v_local: torch.Tensor, l_p: int, *,
+                     return_scores: bool = False, workspace: Optional[torch.Tensor] = None,
+                     idx_out: Optional[torch.Tensor] = None, k_c_out: Optional[torch.Tensor] = None,
+                     v_c_out: Optional[torch.Tensor] = None, scores_out: Optional[torch.Tensor] = None,
+                     stream: Optional[torch.cuda.Stream] = None):
+    """Compressed block (idx, K_c, V_c[, scores]) of one context block; see apbv_compress_kv in
+    include/apbv.h.  Tensors are ``[tokens, heads, d]`` or batched ``[batch, tokens, heads, d]``."""
+    lib = load_library()
+    batched = k_local.dim() == 4
+    qv, bq = tensor_view(q_probe)
+    kv, b = tensor_view(k_local)
+    vv, bv = tensor_view(v_local)
+    if not (bq == b == bv):
+        raise ValueError("batch sizes differ")
+    hq, d = q_probe.shape[-2], q_probe.shape[-1]
+    hkv, L = k_local.shape[-2], k_local.shape[-3]
+    dev = k_local.device
+    if idx_out is None:
+        idx_out = torch.empty((b, hkv, l_p), dtype=torch.int32, device=dev)
+    if k_c_out is None:
+        k_c_out = torch.empty((b, l_p, hkv, d), dtype=torch.bfloat16, device=dev)
+    if v_c_out is None:
+        v_c_out = torch.empty((b, l_p, hkv, d), dtype=torch.bfloat16, device=dev)
+    if return_scores and scores_out is None:
+        scores_out = torch.empty((b, hkv, L), dtype=torch.float64, device=dev)
+    if workspace is None:
+        nbytes = max(apbv_compress_workspace_bytes(b, hkv, d, L, l_p), 256)
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    st = lib.apbv_compress_kv(
+        b, hq, hkv, d, qv, kv, vv, int(l_p),
+        idx_out.data_ptr() if l_p > 0 else None, k_c_out.data_ptr() if l_p > 0 else None,
+        v_c_out.data_ptr() if l_p > 0 else None,
+        scores_out.data_ptr() if scores_out is not None else None,
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    if st != 0:
+        raise ApbvError(st, "apbv_compress_kv")
+    if not batched:
+        idx_out, k_c_out, v_c_out = idx_out[0], k_c_out[0], v_c_out[0]
+        scores_out = scores_out[0] if scores_out is not None else None
+    if return_scores:
+        return idx_out, k_c_out, v_c_out, scores_out
+    return idx_out, k_c_out, v_c_out
+
+
+def apbv_host_attention(q_local: torch.Tensor, k_anchor: torch.Tensor, v_anchor: torch.Tensor,
+                        k_pass: torch.Tensor, v_pass: torch.Tensor, k_local: torch.Tensor, v_local: torch.Tensor,
+                        softmax_scale: float, *, return_lse: bool = False, out: Optional[torch.Tensor] = None,
+                        lse_out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """Fused host attention over [anchor | passing | local(causal)]; see apbv_host_attention in
+    include/apbv.h.  Returns ``out [.., L, Hq, d]`` bf16 (and ``lse [.., Hq, L]`` fp32)."""
+    lib = load_library()
+    batched = q_local.dim() == 4
+    views = []
+    b = None
+    for t in (q_local, k_anchor, v_anchor, k_pass, v_pass, k_local, v_local):
+        view, bt = tensor_view(t)
+        if b is None:
+            b = bt
+        elif bt != b:
+            raise ValueError("batch sizes differ")
+        views.append(view)
+    L, hq, d = q_local.shape[-3], q_local.shape[-2], q_local.shape[-1]
+    hkv = k_local.shape[-2]
+    dev = q_local.device
+    if out is None:
+        out = torch.empty((b, L, hq, d), dtype=torch.bfloat16, device=dev)
+    if return_lse and lse_out is None:
+        lse_out = torch.empty((b, hq, L), dtype=torch.float32, device=dev)
+    st = lib.apbv_host_attention(b, hq, hkv, d, *views, float(softmax_scale), out.data_ptr(),
+                                 lse_out.data_ptr() if lse_out is not None else None, _stream_ptr(stream))
+    if st != 0:
+        raise ApbvError(st, "apbv_host_attention")
+    if not batched:
+        out = out[0] if out.dim() == 4 else out
+        lse_out = lse_out[0] if (lse_out is not None and lse_out.dim() == 3) else lse_out
+    return (out, lse_out) if return_lse else out

@@ -1,0 +1,72 @@
+// Shared device/host declarations of the gfx950 library (internal; the public ABI is include/apbv.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "apbv.h"
+
+namespace apbv {
+
+typedef uint16_t bf16_t;                                                  // bf16 bit pattern
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;                // one MFMA A/B operand
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;                // one 32x32 MFMA accumulator
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;               // 16 bytes
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;               // 8 bytes
+
+// A [tokens, heads, d] bf16 view already offset to nothing: base pointer plus element strides.
+struct View {
+  const bf16_t* ptr;
+  int64_t tokens;
+  int64_t st;   // stride_token
+  int64_t sh;   // stride_head
+  int64_t sb;   // stride_batch
+};
+
+inline View to_view(const apbv_tensor& t) {
+  View v;
+  v.ptr = static_cast<const bf16_t*>(t.ptr);
+  v.tokens = t.tokens;
+  v.st = t.stride_token;
+  v.sh = t.stride_head;
+  v.sb = t.stride_batch;
+  return v;
+}
+
+// ---- attention --------------------------------------------------------------------------------
+struct AttnParams {
+  View q;                 // [L, Hq, d]
+  View k_seg[3];          // anchor, passing, local  [*, Hkv, d]
+  View v_seg[3];
+  bf16_t* out;            // [batch, L, Hq, d]
+  float* lse;             // [batch, Hq, L] or nullptr
+  int64_t L;              // local block length
+  int64_t l_a;            // anchor length
+  int64_t n_vis;          // l_a + n_p: keys visible to every query
+  int64_t s_kv;           // n_vis + L
+  int batch, hq, hkv, group;
+  float scale_log2;       // softmax_scale * log2(e)
+};
+
+apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream);
+
+// ---- compression ------------------------------------------------------------------------------
+struct CompressParams {
+  View q_probe;           // [n_q, Hq, d]
+  View k;                 // [L, Hkv, d]
+  View v;
+  int64_t L, l_p;
+  int batch, hq, hkv, group, d;
+  int32_t* idx_out;       // [batch, Hkv, l_p]
+  bf16_t* k_c;            // [batch, l_p, Hkv, d]
+  bf16_t* v_c;
+  double* scores_out;     // optional [batch, Hkv, L]
+  void* workspace;
+  size_t workspace_bytes;
+};
+
+size_t compress_workspace_bytes(int batch, int hkv, int d, int64_t L, int64_t l_p);
+apbv_status launch_compress(const CompressParams& p, hipStream_t stream);
+
+}  // namespace apbv

@@ -1,0 +1,139 @@
+// C ABI of the library: argument validation on the host, then dispatch to the kernel launchers.
+// Nothing is launched when an argument is rejected.
+#include <cmath>
+#include "apbv_common.h"
+
+using namespace apbv;
+
+namespace {
+
+constexpr int64_t kMaxTokens = (int64_t)1 << 24;
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// A view is acceptable if it is empty, or has a 16-byte aligned pointer and strides that keep every
+// (token, head) row 16-byte aligned and non-overlapping along the head dimension.
+apbv_status check_view(const apbv_tensor& t, int heads, int d, int batch, bool may_be_empty) {
+  if (t.tokens < 0 || t.tokens > kMaxTokens) return APBV_ERR_SHAPE;
+  if (t.tokens == 0) return may_be_empty ? APBV_OK : APBV_ERR_SHAPE;
+  if (t.ptr == nullptr) return APBV_ERR_NULL;
+  if (!aligned(t.ptr, 16)) return APBV_ERR_SHAPE;
+  if (t.stride_token < d || t.stride_token % 8) return APBV_ERR_SHAPE;
+  if (heads > 1 && (t.stride_head < d || t.stride_head % 8)) return APBV_ERR_SHAPE;
+  if (batch > 1 && (t.stride_batch <= 0 || t.stride_batch % 8)) return APBV_ERR_SHAPE;
+  return APBV_OK;
+}
+
+apbv_status check_heads(int batch, int hq, int hkv, int d) {
+  if (batch < 1 || hq < 1 || hkv < 1 || batch > 65535 || hq > 65535) return APBV_ERR_SHAPE;
+  if (hq % hkv) return APBV_ERR_SHAPE;
+  if (d != 64 && d != 128) return APBV_ERR_UNSUPPORTED;
+  return APBV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* apbv_status_string(apbv_status s) {
+  switch (s) {
+    case APBV_OK: return "APBV_OK";
+    case APBV_ERR_NULL: return "APBV_ERR_NULL: a required pointer is NULL";
+    case APBV_ERR_SHAPE: return "APBV_ERR_SHAPE: inconsistent or out-of-range sizes or strides";
+    case APBV_ERR_UNSUPPORTED: return "APBV_ERR_UNSUPPORTED: head_dim or size not implemented";
+    case APBV_ERR_WORKSPACE: return "APBV_ERR_WORKSPACE: workspace NULL, misaligned or too small";
+    case APBV_ERR_LAUNCH: return "APBV_ERR_LAUNCH: the HIP runtime refused a kernel launch";
+  }
+  return "unknown apbv_status";
+}
+
+int apbv_version(void) { return 100; }
+
+size_t apbv_compress_workspace_bytes(int batch, int n_kv_heads, int head_dim, int64_t L, int64_t l_p) {
+  if (batch < 1 || n_kv_heads < 1 || (head_dim != 64 && head_dim != 128) || L < 1 || L > kMaxTokens || l_p < 0 || l_p > L)
+    return 0;
+  return compress_workspace_bytes(batch, n_kv_heads, head_dim, L, l_p);
+}
+
+apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_probe,
+                             apbv_tensor k_local, apbv_tensor v_local, int64_t l_p, int32_t* idx_out, void* k_c_out,
+                             void* v_c_out, double* scores_out, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
+  if (st != APBV_OK) return st;
+  if ((st = check_view(q_probe, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if (v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
+  const int64_t L = k_local.tokens;
+  if (l_p < 0 || l_p > L) return APBV_ERR_SHAPE;
+  if (l_p > 0) {
+    if (idx_out == nullptr || k_c_out == nullptr || v_c_out == nullptr) return APBV_ERR_NULL;
+    if (!aligned(k_c_out, 16) || !aligned(v_c_out, 16) || !aligned(idx_out, 4)) return APBV_ERR_SHAPE;
+  }
+  if (scores_out != nullptr && !aligned(scores_out, 8)) return APBV_ERR_SHAPE;
+  const size_t need = compress_workspace_bytes(batch, n_kv_heads, head_dim, L, l_p);
+  if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) return APBV_ERR_WORKSPACE;
+
+  CompressParams p;
+  p.q_probe = to_view(q_probe);
+  p.k = to_view(k_local);
+  p.v = to_view(v_local);
+  p.L = L;
+  p.l_p = l_p;
+  p.batch = batch;
+  p.hq = n_q_heads;
+  p.hkv = n_kv_heads;
+  p.group = n_q_heads / n_kv_heads;
+  p.d = head_dim;
+  p.idx_out = idx_out;
+  p.k_c = static_cast<bf16_t*>(k_c_out);
+  p.v_c = static_cast<bf16_t*>(v_c_out);
+  p.scores_out = scores_out;
+  p.workspace = workspace;
+  p.workspace_bytes = workspace_bytes;
+  return launch_compress(p, static_cast<hipStream_t>(hip_stream));
+}
+
+apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_local,
+                                apbv_tensor k_anchor, apbv_tensor v_anchor, apbv_tensor k_pass, apbv_tensor v_pass,
+                                apbv_tensor k_local, apbv_tensor v_local, float softmax_scale, void* out,
+                                float* lse_out, void* hip_stream) {
+  apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
+  if (st != APBV_OK) return st;
+  if ((st = check_view(q_local, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(k_anchor, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
+  if ((st = check_view(v_anchor, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
+  if ((st = check_view(k_pass, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
+  if ((st = check_view(v_pass, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
+  if (q_local.tokens != k_local.tokens || v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
+  if (v_anchor.tokens != k_anchor.tokens || v_pass.tokens != k_pass.tokens) return APBV_ERR_SHAPE;
+  if (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale)) return APBV_ERR_SHAPE;
+  if (out == nullptr) return APBV_ERR_NULL;
+  if (!aligned(out, 16) || (lse_out != nullptr && !aligned(lse_out, 4))) return APBV_ERR_SHAPE;
+
+  AttnParams p;
+  p.q = to_view(q_local);
+  p.k_seg[0] = to_view(k_anchor);
+  p.k_seg[1] = to_view(k_pass);
+  p.k_seg[2] = to_view(k_local);
+  p.v_seg[0] = to_view(v_anchor);
+  p.v_seg[1] = to_view(v_pass);
+  p.v_seg[2] = to_view(v_local);
+  p.out = static_cast<bf16_t*>(out);
+  p.lse = lse_out;
+  p.L = k_local.tokens;
+  p.l_a = k_anchor.tokens;
+  p.n_vis = k_anchor.tokens + k_pass.tokens;
+  p.s_kv = p.n_vis + p.L;
+  p.batch = batch;
+  p.hq = n_q_heads;
+  p.hkv = n_kv_heads;
+  p.group = n_q_heads / n_kv_heads;
+  p.scale_log2 = softmax_scale * 1.4426950408889634f;
+  return launch_host_attention(p, head_dim, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,373 @@
+// KV compression for gfx950 (Sec. 3.3; Alg. 1 "Identify Essential KVs" and "Send Block's Essential
+// KVs"): score every local key, keep the l_p best per KV head, gather them.
+//
+// The score of key j for KV head v is the sum of the raw logits Q_qr[t, v*G+g] . K[j, v] over all
+// query-block rows t and the G query heads of the group.  The sum is linear in the query, so it is
+// evaluated as  q_bar[v] . K[j, v]  with the pooled query q_bar[v] = sum_t sum_g Q_qr[t, v*G+g]:
+// one streaming pass over K, bound by HBM bandwidth.  Accumulation is in float64 so that the ranking
+// agrees with a float64 evaluation (float32 accumulation flips near-equal neighbours).
+//
+// Four launches on the caller's stream:
+//   pool_query_kernel   q_bar (float64)                                   [Hkv x batch workgroups]
+//   score_kernel        s[v, j], 16-byte coalesced reads of K rows        [L/64 x Hkv x batch]
+//   select_kernel       radix select of the l_p-th largest key + bitonic sort of the winners into
+//                       (score descending, index ascending) order         [Hkv x batch]
+//   gather_kernel       K_c, V_c rows                                     [l_p*Hkv/.. x batch]
+#include <mutex>
+#include "apbv_common.h"
+
+namespace apbv {
+namespace {
+
+constexpr int kSelectThreads = 1024;
+constexpr int64_t kLdsSortMax = 8192;          // winners that fit the LDS sort (12 bytes each)
+
+__host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline int64_t pow2_ceil(int64_t x) {
+  int64_t n = 1;
+  while (n < x) n <<= 1;
+  return n;
+}
+
+struct Workspace {
+  size_t qbar_off, scores_off, sort_keys_off, sort_idx_off, total;
+  int64_t n_sort;       // padded number of sorted entries
+  bool sort_in_global;
+};
+
+Workspace plan_workspace(int batch, int hkv, int d, int64_t L, int64_t l_p) {
+  Workspace w;
+  size_t off = 0;
+  w.qbar_off = off;
+  off = align_up(off + (size_t)batch * hkv * d * sizeof(double), 256);
+  w.scores_off = off;
+  off = align_up(off + (size_t)batch * hkv * (size_t)L * sizeof(double), 256);
+  w.n_sort = pow2_ceil(l_p > 1 ? l_p : 1);
+  w.sort_in_global = w.n_sort > kLdsSortMax;
+  w.sort_keys_off = w.sort_idx_off = off;
+  if (w.sort_in_global) {
+    w.sort_keys_off = off;
+    off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * sizeof(uint64_t), 256);
+    w.sort_idx_off = off;
+    off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * sizeof(uint32_t), 256);
+  }
+  w.total = off;
+  return w;
+}
+
+__device__ __forceinline__ double bf16_to_f64(uint32_t bits16) {
+  return (double)__uint_as_float(bits16 << 16);
+}
+
+// ------------------------------------------------------------------------------------------------
+// q_bar[b, v, c] = sum_g sum_t Q_qr[b, t, v*G+g, c]   (float64; the addends are bf16 so the sum is
+// exact or within an ulp whatever the order)
+__global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, int group, int d, double* qbar, int hkv) {
+  __shared__ double part[1024];
+  const int v = blockIdx.x, b = blockIdx.y;
+  const int c = threadIdx.x % d;
+  const int slice = threadIdx.x / d, n_slices = blockDim.x / d;
+  const bf16_t* base = q.ptr + (int64_t)b * q.sb + (int64_t)v * group * q.sh + c;
+  double acc = 0.0;
+  for (int64_t t = slice; t < n_q; t += n_slices)
+    for (int g = 0; g < group; ++g) acc += bf16_to_f64(base[t * q.st + (int64_t)g * q.sh]);
+  part[threadIdx.x] = acc;
+  __syncthreads();
+  if (slice == 0) {
+    for (int s = 1; s < n_slices; ++s) acc += part[s * d + c];
+    qbar[((int64_t)b * hkv + v) * d + c] = acc;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// s[b, v, j] = q_bar[b, v, :] . K[b, j, v, :].  D/8 lanes per key row, each lane 8 elements (one
+// 16-byte load), fixed summation order per row so identical rows get identical scores.
+template <int D>
+__global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const double* __restrict__ qbar,
+                                                    double* __restrict__ s_ws, double* __restrict__ s_out,
+                                                    int hkv, int rows_per_block) {
+  constexpr int LPR = D / 8;               // lanes per row
+  constexpr int RPS = 256 / LPR;           // rows per step of the workgroup
+  constexpr int UNROLL = 4;
+  const int v = blockIdx.y, b = blockIdx.z;
+  const int c = threadIdx.x % LPR;
+  const int rsub = threadIdx.x / LPR;
+  const double* qb = qbar + ((int64_t)b * hkv + v) * D + 8 * c;
+  double qv[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) qv[e] = qb[e];
+  const bf16_t* base = k.ptr + (int64_t)b * k.sb + (int64_t)v * k.sh + 8 * c;
+  const int64_t out_base = ((int64_t)b * hkv + v) * L;
+  const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
+  const int64_t r_end = (r_begin + rows_per_block < L) ? r_begin + rows_per_block : L;
+
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += RPS * UNROLL) {
+    u32x4 x[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      const int64_t j = r0 + u * RPS + rsub;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      if (j < r_end) z = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + j * k.st));
+      x[u] = z;
+    }
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) {
+      double acc = 0.0;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc = __builtin_fma(qv[2 * e], bf16_to_f64(x[u][e] & 0xffffu), acc);
+        acc = __builtin_fma(qv[2 * e + 1], bf16_to_f64(x[u][e] >> 16), acc);
+      }
+#pragma unroll
+      for (int m = 1; m < LPR; m <<= 1) acc += __shfl_xor(acc, m);
+      const int64_t j = r0 + u * RPS + rsub;
+      if (c == 0 && j < r_end) {
+        s_ws[out_base + j] = acc;
+        if (s_out) s_out[out_base + j] = acc;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Order-preserving key: larger score <=> larger unsigned key; -0.0 and +0.0 map to the same key.
+__device__ __forceinline__ uint64_t score_key(double s) {
+  uint64_t b = (uint64_t)__double_as_longlong(s);
+  if ((b << 1) == 0) b = 0;
+  return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+}
+
+// (key descending, index ascending)
+__device__ __forceinline__ bool precedes(uint64_t ka, uint32_t ia, uint64_t kb, uint32_t ib) {
+  return ka > kb || (ka == kb && ia < ib);
+}
+
+// One workgroup per (KV head, batch item).  skeys/sidx hold n_sort entries (LDS or global).
+template <bool kGlobalSort>
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __restrict__ s_ws, int64_t L, int64_t l_p,
+                                                                int64_t n_sort, int32_t* __restrict__ idx_out,
+                                                                uint64_t* gkeys, uint32_t* gidx, int hkv) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
+  __shared__ uint32_t hist[256];
+  __shared__ uint64_t sh_prefix;
+  __shared__ uint32_t sh_need, sh_bucket, sh_cnt;
+  __shared__ uint32_t wave_tot[kSelectThreads / 64];
+
+  const int v = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int64_t head = (int64_t)b * hkv + v;
+  const double* s = s_ws + head * L;
+  uint64_t* skeys;
+  uint32_t* sidx;
+  if (kGlobalSort) {
+    skeys = gkeys + head * n_sort;
+    sidx = gidx + head * n_sort;
+  } else {
+    skeys = reinterpret_cast<uint64_t*>(dyn);
+    sidx = reinterpret_cast<uint32_t*>(dyn + n_sort * sizeof(uint64_t));
+  }
+
+  // ---- radix select, most significant byte first: after 8 passes `prefix` is the l_p-th largest key
+  // and `need` says how many keys equal to it belong to the result.
+  uint64_t prefix = 0;
+  uint32_t need = (uint32_t)l_p;
+  uint32_t bucket = 0;           // number of keys equal to the final prefix
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    for (int64_t j = tid; j < L; j += kSelectThreads) {
+      const uint64_t key = score_key(s[j]);
+      if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // lane l owns digits 255-4l .. 252-4l (descending); find the digit holding the need-th largest
+      uint32_t c4[4], tot = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        c4[q] = hist[255 - 4 * lane - q];
+        tot += c4[q];
+      }
+      uint32_t incl = tot;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+      }
+      uint32_t excl = incl - tot;
+      if (excl < need && need <= incl) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (excl < need && need <= excl + c4[q]) {
+            sh_prefix = (prefix << 8) | (uint64_t)(255 - 4 * lane - q);
+            sh_need = need - excl;
+            sh_bucket = c4[q];
+          }
+          excl += c4[q];
+        }
+      }
+    }
+    __syncthreads();
+    prefix = sh_prefix;
+    need = sh_need;
+    bucket = sh_bucket;
+  }
+  const uint64_t kth = prefix;
+  const uint32_t n_gt = (uint32_t)l_p - need;     // keys strictly above the threshold
+
+  // ---- collect the winners (unordered above the threshold; ties at the threshold by index)
+  if (tid == 0) sh_cnt = 0;
+  for (int64_t i = l_p + tid; i < n_sort; i += kSelectThreads) {   // padding sorts last
+    skeys[i] = 0;
+    sidx[i] = 0xffffffffu;
+  }
+  __syncthreads();
+  if (bucket == need) {
+    // every key equal to the threshold is taken: no ordering constraint while collecting
+    for (int64_t j = tid; j < L; j += kSelectThreads) {
+      const uint64_t key = score_key(s[j]);
+      if (key >= kth) {
+        const uint32_t pos = atomicAdd(&sh_cnt, 1u);
+        skeys[pos] = key;
+        sidx[pos] = (uint32_t)j;
+      }
+    }
+  } else {
+    // more equal keys than needed: take the `need` lowest indices.  Each thread scans a contiguous
+    // index range; an exclusive scan of the per-thread tie counts gives each tie its rank by index.
+    const int64_t chunk = (L + kSelectThreads - 1) / kSelectThreads;
+    const int64_t lo = (int64_t)tid * chunk, hi = (lo + chunk < L) ? lo + chunk : L;
+    uint32_t n_eq = 0;
+    for (int64_t j = lo; j < hi; ++j) n_eq += (score_key(s[j]) == kth);
+    uint32_t incl = n_eq;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const uint32_t o = __shfl_up(incl, off);
+      if (lane >= off) incl += o;
+    }
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    uint32_t rank = incl - n_eq;
+    for (int w = 0; w < wave; ++w) rank += wave_tot[w];
+    for (int64_t j = lo; j < hi; ++j) {
+      const uint64_t key = score_key(s[j]);
+      if (key > kth) {
+        const uint32_t pos = atomicAdd(&sh_cnt, 1u);
+        skeys[pos] = key;
+        sidx[pos] = (uint32_t)j;
+      } else if (key == kth) {
+        if (rank < need) {
+          skeys[n_gt + rank] = key;
+          sidx[n_gt + rank] = (uint32_t)j;
+        }
+        ++rank;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- bitonic sort of n_sort entries into (key descending, index ascending) order
+  for (int64_t k = 2; k <= n_sort; k <<= 1) {
+    for (int64_t j = k >> 1; j > 0; j >>= 1) {
+      for (int64_t pidx = tid; pidx < (n_sort >> 1); pidx += kSelectThreads) {
+        const int64_t i = ((pidx / j) * 2 * j) + (pidx % j);
+        const int64_t q = i + j;
+        const bool up = (i & k) == 0;          // this run is sorted "first precedes"
+        const uint64_t ka = skeys[i], kb = skeys[q];
+        const uint32_t ia = sidx[i], ib = sidx[q];
+        const bool in_order = precedes(ka, ia, kb, ib);
+        if (in_order != up) {
+          skeys[i] = kb;
+          skeys[q] = ka;
+          sidx[i] = ib;
+          sidx[q] = ia;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  for (int64_t i = tid; i < l_p; i += kSelectThreads) idx_out[head * l_p + i] = (int32_t)sidx[i];
+}
+
+// ------------------------------------------------------------------------------------------------
+// K_c[b, i, v, :] = K[b, idx[b, v, i], v, :], same for V.  One thread per 16-byte chunk.
+template <int D>
+__global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32_t* __restrict__ idx, int64_t l_p, int hkv,
+                                                     bf16_t* __restrict__ k_c, bf16_t* __restrict__ v_c) {
+  constexpr int KC = D / 8;
+  const int b = blockIdx.y;
+  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;      // over l_p * hkv * KC
+  const int64_t n_items = l_p * hkv * KC;
+  if (item >= n_items) return;
+  const int c = (int)(item % KC);
+  const int64_t row = item / KC;            // i * hkv + head
+  const int head = (int)(row % hkv);
+  const int64_t i = row / hkv;
+  const int64_t j = idx[((int64_t)b * hkv + head) * l_p + i];
+  const int64_t dst = (((int64_t)b * l_p + i) * hkv + head) * D + 8 * c;
+  const u32x4 kk = *reinterpret_cast<const u32x4*>(k.ptr + (int64_t)b * k.sb + j * k.st + (int64_t)head * k.sh + 8 * c);
+  const u32x4 vv = *reinterpret_cast<const u32x4*>(v.ptr + (int64_t)b * v.sb + j * v.st + (int64_t)head * v.sh + 8 * c);
+  *reinterpret_cast<u32x4*>(k_c + dst) = kk;
+  *reinterpret_cast<u32x4*>(v_c + dst) = vv;
+}
+
+std::once_flag g_attr_once;
+
+}  // namespace
+
+size_t compress_workspace_bytes(int batch, int hkv, int d, int64_t L, int64_t l_p) {
+  return plan_workspace(batch, hkv, d, L, l_p).total;
+}
+
+apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
+  const Workspace w = plan_workspace(p.batch, p.hkv, p.d, p.L, p.l_p);
+  if (p.workspace_bytes < w.total) return APBV_ERR_WORKSPACE;
+  unsigned char* ws = static_cast<unsigned char*>(p.workspace);
+  double* qbar = reinterpret_cast<double*>(ws + w.qbar_off);
+  double* scores = reinterpret_cast<double*>(ws + w.scores_off);
+
+  // pooled query
+  {
+    int threads = 1024;   // a multiple of d for d in {64, 128}
+    hipLaunchKernelGGL(pool_query_kernel, dim3(p.hkv, p.batch), dim3(threads), 0, stream, p.q_probe, p.q_probe.tokens,
+                       p.group, p.d, qbar, p.hkv);
+  }
+  // scores
+  {
+    // one outer iteration per workgroup: 4 rows in flight per thread, many small workgroups
+    const int rows_per_block = 4 * 256 / (p.d / 8);
+    dim3 grid((unsigned)((p.L + rows_per_block - 1) / rows_per_block), p.hkv, p.batch);
+    if (p.d == 128)
+      hipLaunchKernelGGL(score_kernel<128>, grid, dim3(256), 0, stream, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
+    else
+      hipLaunchKernelGGL(score_kernel<64>, grid, dim3(256), 0, stream, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
+  }
+  if (p.l_p > 0) {
+    // select + order
+    if (w.sort_in_global) {
+      hipLaunchKernelGGL(select_kernel<true>, dim3(p.hkv, p.batch), dim3(kSelectThreads), 0, stream, scores, p.L, p.l_p,
+                         w.n_sort, p.idx_out, reinterpret_cast<uint64_t*>(ws + w.sort_keys_off),
+                         reinterpret_cast<uint32_t*>(ws + w.sort_idx_off), p.hkv);
+    } else {
+      std::call_once(g_attr_once, [] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsSortMax * 12));
+      });
+      const size_t dyn = (size_t)w.n_sort * 12;
+      hipLaunchKernelGGL(select_kernel<false>, dim3(p.hkv, p.batch), dim3(kSelectThreads), dyn, stream, scores, p.L, p.l_p,
+                         w.n_sort, p.idx_out, nullptr, nullptr, p.hkv);
+    }
+    // gather
+    const int64_t n_items = p.l_p * p.hkv * (p.d / 8);
+    dim3 grid((unsigned)((n_items + 255) / 256), p.batch);
+    if (p.d == 128)
+      hipLaunchKernelGGL(gather_kernel<128>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.k_c, p.v_c);
+    else
+      hipLaunchKernelGGL(gather_kernel<64>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.k_c, p.v_c);
+  }
+  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+}
+
+}  // namespace apbv

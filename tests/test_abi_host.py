@@ -1,0 +1,109 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports exactly the symbols
+include/apbv.h declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2601_21444_amd as apbv
+from paper_2601_21444_amd.binding import ApbvTensor
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "apbv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(apbv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = apbv.load_library()
+    names = declared_symbols()
+    assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention",
+                     "apbv_status_string", "apbv_version"]
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert apbv.apbv_version() >= 100
+
+
+def test_status_strings():
+    for code, word in [(0, "OK"), (-1, "NULL"), (-2, "SHAPE"), (-3, "UNSUPPORTED"), (-4, "WORKSPACE"), (-5, "LAUNCH")]:
+        assert word in apbv.status_string(code)
+    assert "unknown" in apbv.status_string(-99)
+
+
+def test_workspace_size_query():
+    ws = apbv.apbv_compress_workspace_bytes
+    assert ws(1, 2, 128, 16384, 1024) >= 2 * 16384 * 8 + 2 * 128 * 8
+    assert ws(2, 2, 128, 16384, 1024) > ws(1, 2, 128, 16384, 1024)
+    assert ws(1, 2, 128, 16384, 16384) > ws(1, 2, 128, 16384, 8192)     # large sort spills to the workspace
+    assert ws(1, 2, 96, 16384, 10) == 0 and ws(0, 2, 128, 10, 1) == 0 and ws(1, 2, 128, 10, 11) == 0
+
+
+def view(tokens, heads, d, ptr=0x1000, batch_stride=None):
+    return ApbvTensor(ptr if tokens else None, tokens, heads * d, d, batch_stride or max(tokens, 1) * heads * d)
+
+
+def call_attention(batch=1, hq=4, hkv=2, d=128, L=64, l_a=8, n_p=8, scale=0.1, out=0x2000, q=None, ka=None, va=None,
+                   kp=None, vp=None, k=None, v=None):
+    lib = apbv.load_library()
+    return lib.apbv_host_attention(
+        batch, hq, hkv, d,
+        q or view(L, hq, d), ka or view(l_a, hkv, d), va or view(l_a, hkv, d), kp or view(n_p, hkv, d),
+        vp or view(n_p, hkv, d), k or view(L, hkv, d), v or view(L, hkv, d),
+        ctypes.c_float(scale), out, None, None)
+
+
+def test_attention_rejects_bad_arguments_without_launching():
+    assert call_attention(hq=3, hkv=2) == -2                     # Hq % Hkv
+    assert call_attention(d=96) == -3                            # unsupported head_dim
+    assert call_attention(batch=0) == -2
+    assert call_attention(out=None) == -1
+    assert call_attention(out=0x2004) == -2                      # misaligned output
+    assert call_attention(scale=0.0) == -2 and call_attention(scale=float("nan")) == -2
+    assert call_attention(q=view(63, 4, 128)) == -2              # q rows != local keys
+    assert call_attention(va=view(7, 2, 128)) == -2              # K/V anchor mismatch
+    assert call_attention(vp=view(9, 2, 128)) == -2
+    assert call_attention(k=ApbvTensor(None, 64, 256, 128, 0)) == -1
+    assert call_attention(k=ApbvTensor(0x1008, 64, 256, 128, 0)) == -2      # 8-byte aligned only
+    assert call_attention(k=ApbvTensor(0x1000, 64, 252, 128, 0)) == -2      # stride not a multiple of 8
+    assert call_attention(k=ApbvTensor(0x1000, 64, 64, 128, 0)) == -2       # rows overlap
+    assert call_attention(L=0) == -2
+
+
+def call_compress(batch=1, hq=4, hkv=2, d=128, n_q=4, L=64, l_p=8, idx=0x3000, kc=0x4000, vc=0x5000, ws=0x10000,
+                  ws_bytes=1 << 20, q=None, k=None, v=None):
+    lib = apbv.load_library()
+    return lib.apbv_compress_kv(batch, hq, hkv, d, q or view(n_q, hq, d), k or view(L, hkv, d), v or view(L, hkv, d),
+                                l_p, idx, kc, vc, None, ws, ws_bytes, None)
+
+
+def test_compress_rejects_bad_arguments_without_launching():
+    assert call_compress(l_p=65) == -2 and call_compress(l_p=-1) == -2
+    assert call_compress(hq=5) == -2
+    assert call_compress(d=32) == -3
+    assert call_compress(idx=None) == -1 and call_compress(kc=None) == -1 and call_compress(vc=None) == -1
+    assert call_compress(ws=None) == -4 and call_compress(ws=0x10010) == -4 and call_compress(ws_bytes=64) == -4
+    assert call_compress(n_q=0) == -2
+    assert call_compress(v=view(63, 2, 128)) == -2
+    assert call_compress(kc=0x4002) == -2
+
+
+def test_product_path_has_no_oracle_or_cpu_fallback():
+    """The package must not import the oracle, and must raise when the library is absent."""
+    pkg = os.path.join(ROOT, "paper_2601_21444_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", src, flags=re.M), f
+    import paper_2601_21444_amd.binding as b
+    saved_lib, saved_path = b._lib, b._LIB_PATH
+    try:
+        b._lib, b._LIB_PATH = None, os.path.join(pkg, "does_not_exist.so")
+        with pytest.raises(RuntimeError, match="no CPU or PyTorch fallback"):
+            b.load_library()
+    finally:
+        b._lib, b._LIB_PATH = saved_lib, saved_path
