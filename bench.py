@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the APB-V host-share hot path on one MI355X.
+
+One "step" = one layer's hot path for one virtual host at the headline workload: apbv_compress_kv on the
+local context block (batch 1) followed by apbv_host_attention over [anchor | passing | local(causal)].
+Inputs are synthetic (seeded, Qwen2.5-VL-3B-shaped; see paper_2601_21444_amd/workloads.py) and resident
+in HBM before the timed region.  The passing blocks that preceding hosts would send are produced, untimed,
+by running the same compression kernel on their generated context blocks.
+
+Prints ONE JSON line.  `value` is the useful attention FLOP rate of the whole step (visible (q,k)
+pairs x 4d flops, divided by the wall time of compress + attention).  `roofline` describes the dominant
+kernel (attention, bf16 MFMA bound) from HIP-event timings taken inside the timed region;
+`roofline_compress` describes the score/select/gather pipeline at a batch whose working set exceeds the
+256 MB last-level cache (HBM bound); `cpu_baseline` is the fp64 oracle timed on this machine's host cores on
+a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E, published
+
+# HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# each scaled by the same counter's reading for a copy kernel of known size; see profiles/.  None until
+# measured.
+MEASURED_TRAFFIC_BYTES = None
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None, help="workload name (default: the headline config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-compress-roofline", action="store_true")
+    ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows the oracle is timed on")
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build covers one GPU (one virtual host's share); --gpus N with N > 1 is not "
+              "supported -- the sequence-parallel exchange between hosts is outside the single-GPU hot path.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2601_21444_amd as apbv
+    from paper_2601_21444_amd import workloads as wl
+
+    apbv.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    name = args.workload or wl.HEADLINE
+    cfg = wl.CONFIGS[name]
+    x = wl.generate(cfg)
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+    q_probe, q, k_a, v_a, k, v = (dev(a) for a in (x.q_probe, x.q, x.k_anchor, x.v_anchor, x.k, x.v))
+    scale = 1.0 / math.sqrt(cfg.head_dim)
+
+    # Passing block = compressed blocks of the preceding hosts (what the all-gather would deliver).
+    kps, vps = [], []
+    for kb, vb in zip(x.k_prev, x.v_prev):
+        _, a, b = apbv.apbv_compress_kv(q_probe, dev(kb), dev(vb), cfg.l_p)
+        kps.append(a)
+        vps.append(b)
+    empty = torch.empty((0, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    k_p = torch.cat(kps) if kps else empty
+    v_p = torch.cat(vps) if vps else empty
+    torch.cuda.synchronize()
+
+    # Pre-allocated outputs and workspace: nothing is allocated inside the timed region.
+    ws = torch.empty(max(apbv.apbv_compress_workspace_bytes(1, cfg.n_kv_heads, cfg.head_dim, cfg.L, cfg.l_p), 256),
+                     dtype=torch.uint8, device="cuda")
+    idx = torch.empty((1, cfg.n_kv_heads, cfg.l_p), dtype=torch.int32, device="cuda")
+    k_c = torch.empty((1, cfg.l_p, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_c = torch.empty_like(k_c)
+    out = torch.empty((1, cfg.L, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+
+    def step(ev=None):
+        if ev:
+            ev[0].record()
+        apbv.apbv_compress_kv(q_probe, k, v, cfg.l_p, workspace=ws, idx_out=idx, k_c_out=k_c, v_c_out=v_c)
+        if ev:
+            ev[1].record()
+        apbv.apbv_host_attention(q, k_a, v_a, k_p, v_p, k, v, scale, out=out)
+        if ev:
+            ev[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    comp_ms = sorted(e[0].elapsed_time(e[1]) for e in events)
+    attn_ms = sorted(e[1].elapsed_time(e[2]) for e in events)
+    attn_avg_ms = sum(attn_ms) / len(attn_ms)
+    comp_avg_ms = sum(comp_ms) / len(comp_ms)
+    flops = cfg.attention_flops
+    attn_tflops = flops / (attn_avg_ms * 1e-3) / 1e12
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    result = {
+        "metric": "host-share attention TFLOP/s (% bf16 MFMA peak) + compress GB/s, ms/layer",
+        "value": round(value, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"{name}: Hq {cfg.n_q_heads} / Hkv {cfg.n_kv_heads} / d {cfg.head_dim}, local {cfg.L}, anchor {cfg.l_a}, "
+                        f"{cfg.P} passing blocks of top-{cfg.l_p}, probe n_q {cfg.n_q}, batch 1",
+            "attention_flops": flops,
+            "compress_bytes": cfg.compress_bytes,
+        },
+        "ms_per_layer": round(ms_per_step, 4),
+        "attention": {"ms_avg": round(attn_avg_ms, 4), "ms_median": round(attn_ms[len(attn_ms) // 2], 4),
+                      "ms_min": round(attn_ms[0], 4), "ms_max": round(attn_ms[-1], 4),
+                      "tflops": round(attn_tflops, 2), "pct_bf16_mfma_peak": round(100 * attn_tflops / PEAK_BF16_MFMA_TFLOPS, 2)},
+        "compress_batch1": {"us_avg": round(comp_avg_ms * 1e3, 2), "us_median": round(comp_ms[len(comp_ms) // 2] * 1e3, 2),
+                            "us_min": round(comp_ms[0] * 1e3, 2),
+                            "gbps": round(cfg.compress_bytes / (comp_avg_ms * 1e-3) / 1e9, 2)},
+        "roofline": {"bound": "mfma", "kernel": "host_attention_kernel", "achieved": round(attn_tflops, 2),
+                     "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_MFMA_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES},
+    }
+
+    if not args.no_compress_roofline:
+        result["roofline_compress"] = compress_roofline(apbv, torch, cfg, q_probe, k, v)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(np, x, cfg, scale, args.cpu_rows)
+    print(json.dumps(result), flush=True)
+
+
+def compress_roofline(apbv, torch, cfg, q_probe, k, v):
+    """Compression at a batch whose rotating working set exceeds the 256 MB last-level cache, so the
+    K stream really comes from HBM: two buffer sets of `batch` copies each, alternated."""
+    batch = 48
+    sets = []
+    for s in range(2):
+        kb = k.unsqueeze(0).repeat(batch, 1, 1, 1)
+        vb = v.unsqueeze(0).repeat(batch, 1, 1, 1)
+        # decorrelate the copies a little so no two rows of the batch are the same cache lines
+        kb = kb.roll(shifts=s + 1, dims=1).contiguous()
+        sets.append((kb, vb))
+    qp = q_probe.unsqueeze(0).repeat(batch, 1, 1, 1)
+    ws = torch.empty(apbv.apbv_compress_workspace_bytes(batch, cfg.n_kv_heads, cfg.head_dim, cfg.L, cfg.l_p),
+                     dtype=torch.uint8, device="cuda")
+    idx = torch.empty((batch, cfg.n_kv_heads, cfg.l_p), dtype=torch.int32, device="cuda")
+    k_c = torch.empty((batch, cfg.l_p, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    v_c = torch.empty_like(k_c)
+    iters = 20
+    for i in range(4):
+        kb, vb = sets[i % 2]
+        apbv.apbv_compress_kv(qp, kb, vb, cfg.l_p, workspace=ws, idx_out=idx, k_c_out=k_c, v_c_out=v_c)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        kb, vb = sets[i % 2]
+        apbv.apbv_compress_kv(qp, kb, vb, cfg.l_p, workspace=ws, idx_out=idx, k_c_out=k_c, v_c_out=v_c)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    nbytes = cfg.compress_bytes * batch
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": "pool+score+select+gather", "batch": batch, "achieved": round(gbps, 1),
+            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
+            "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes, "traffic": None}
+
+
+def cpu_baseline(np, x, cfg, scale, n_rows):
+    """The fp64 oracle as it stands, on this machine's host cores, on a bounded sample: the whole
+    compression of the local block, and complete attention rows for an evenly spaced subset of query
+    positions (all heads).  Reported as useful TFLOP/s on the same visible-pair FLOP count."""
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    k_p, v_p = oracle.make_passing_block(x.q_probe, x.k_prev, x.v_prev, cfg.l_p, cfg.n_kv_heads, cfg.head_dim)
+    t0 = time.perf_counter()
+    oracle.compress_kv(x.q_probe, x.k, x.v, cfg.l_p)
+    t_comp = time.perf_counter() - t0
+    rows = np.linspace(0, cfg.L - 1, num=min(n_rows, cfg.L)).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.host_attention(x.q, x.k_anchor, x.v_anchor, k_p, v_p, x.k, x.v, scale, rows=rows, chunk=128)
+    t_att = time.perf_counter() - t0
+    n_vis = cfg.l_a + cfg.P * cfg.l_p
+    pairs = int(np.sum(rows + 1 + n_vis))
+    flops = 4 * cfg.head_dim * pairs * cfg.n_q_heads
+    tflops = flops / t_att / 1e12
+    return {"value": round(tflops, 5), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"{len(rows)} evenly spaced query rows of {cfg.L} (all {cfg.n_q_heads} heads, full key rows) in "
+                      f"{t_att:.2f} s; whole-block compress oracle {t_comp * 1e3:.1f} ms "
+                      f"({cfg.compress_bytes / t_comp / 1e9:.3f} GB/s)",
+            "attention_seconds_per_layer_extrapolated": round(cfg.attention_flops / (tflops * 1e12), 2),
+            "compress_seconds_per_layer": round(t_comp, 4)}
+
+
+if __name__ == "__main__":
+    main()

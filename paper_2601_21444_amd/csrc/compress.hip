@@ -295,7 +295,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
 // K_c[b, i, v, :] = K[b, idx[b, v, i], v, :], same for V.  One thread per 16-byte chunk.
 template <int D>
 __global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32_t* __restrict__ idx, int64_t l_p, int hkv,
-                                                     bf16_t* __restrict__ k_c, bf16_t* __restrict__ v_c) {
+                                                     int64_t L, bf16_t* __restrict__ k_c, bf16_t* __restrict__ v_c) {
   constexpr int KC = D / 8;
   const int b = blockIdx.y;
   const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;      // over l_p * hkv * KC
@@ -306,6 +306,7 @@ __global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32
   const int head = (int)(row % hkv);
   const int64_t i = row / hkv;
   const int64_t j = idx[((int64_t)b * hkv + head) * l_p + i];
+  if (j < 0 || j >= L) return;              // never read outside the block, whatever idx holds
   const int64_t dst = (((int64_t)b * l_p + i) * hkv + head) * D + 8 * c;
   const u32x4 kk = *reinterpret_cast<const u32x4*>(k.ptr + (int64_t)b * k.sb + j * k.st + (int64_t)head * k.sh + 8 * c);
   const u32x4 vv = *reinterpret_cast<const u32x4*>(v.ptr + (int64_t)b * v.sb + j * v.st + (int64_t)head * v.sh + 8 * c);
@@ -363,9 +364,9 @@ apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
     const int64_t n_items = p.l_p * p.hkv * (p.d / 8);
     dim3 grid((unsigned)((n_items + 255) / 256), p.batch);
     if (p.d == 128)
-      hipLaunchKernelGGL(gather_kernel<128>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.k_c, p.v_c);
+      hipLaunchKernelGGL(gather_kernel<128>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.L, p.k_c, p.v_c);
     else
-      hipLaunchKernelGGL(gather_kernel<64>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.k_c, p.v_c);
+      hipLaunchKernelGGL(gather_kernel<64>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.L, p.k_c, p.v_c);
   }
   return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
 }
