@@ -1,25 +1,40 @@
 // Fused host attention for gfx950 (Eq. 4 by the definition of Eq. 1): one pass of online-softmax
 // attention of the local query block over the concatenated keys [anchor | passing | local].
 //
-// The three KV segments are walked as ONE virtual key axis j in [0, n_vis + L): anchor and passing
-// keys (j < n_vis) are visible to every query and local key j - n_vis is visible to query i iff
+// Mask.  The three KV segments are walked as ONE virtual key axis j in [0, n_vis + L): anchor and
+// passing keys (j < n_vis) are visible to every query and local key j - n_vis is visible to query i iff
 // j - n_vis <= i, so the whole mask is the single test  j <= i + n_vis  (a causal mask shifted by
-// n_vis).  Key tiles that lie entirely above that diagonal are never visited.
+// n_vis).  Key tiles that lie entirely above that diagonal are never visited, and only tiles that
+// touch it pay for the comparison.
 //
-// Tiling: a workgroup of 4 waves owns 128 consecutive query positions of one query head; each wave
-// owns 32 of them.  Key tiles of 64 virtual keys are staged in LDS: K row-major [64][D] and V
-// transposed [D][64], both with an XOR swizzle of the 16-byte chunks.
+// Tiling.  A workgroup of 4 waves owns 128 consecutive query positions of one query head; each wave
+// owns 32 of them.  Key tiles of 64 virtual keys are copied global -> LDS by the LDS-direct load
+// (global_load_lds_dwordx4: no VGPR staging, no VALU work), double buffered, one barrier per tile.
+// Both K and V are stored row-major [64][D] with an XOR swizzle of their 16-byte chunks; the swizzle is
+// applied on the global side (which chunk a lane fetches), because an LDS-direct load always writes
+// lane l's 16 bytes at base + 16*l.
 //
 // MFMA mapping (v_mfma_f32_32x32x16_bf16; A is 32x16 with lane l holding row l%32, k = 8*(l/32)..+7;
 // B is 16x32 with lane l holding column l%32, same k; D is 32x32 with lane l holding column l%32 and
 // rows 8*(r/4) + 4*(l/32) + r%4 for r = 0..15):
-//   S^T = K Q^T  : A = K tile from LDS (rows = keys), B = Q^T kept in registers (columns = queries).
-//                  Each lane then holds 16 keys of ONE query per 32-key block, so the row maximum and
-//                  row sum of the softmax are in-lane reductions plus one exchange with lane^32.
-//   O^T = V^T P^T: B = P^T taken straight from the S^T accumulator registers (rounded to bf16), no
-//                  LDS round trip.  The k-slot -> key assignment this induces (for the t-th MFMA of a
-//                  32-key block, lane half hh, element e: key 16t + 8*(e/4) + 4*hh + e%4) is baked into
-//                  the order in which V^T is stored in LDS, so A = V^T is one 16-byte LDS read.
+//   S^T = K Q^T  : A = K tile rows (one 16-byte LDS read), B = Q^T kept in registers (columns =
+//                  queries).  Each lane then holds 16 keys of ONE query per 32-key block, so the row
+//                  maximum and row sum of the softmax are in-lane reductions plus one exchange with
+//                  lane^32 (v_permlane32_swap).
+//   O^T = V^T P^T: B = P^T straight from the S^T accumulator registers (rounded to bf16), no LDS round
+//                  trip.  That fixes which key sits in which k-slot (t-th MFMA of a 32-key block, lane
+//                  half hh, element e: key 16t + 8*(e/4) + 4*hh + e%4); A = V^T is fetched to match with
+//                  two transposing LDS reads (ds_read_b64_tr_b16: within 16 lanes, lane i receives
+//                  element i%4 of the 8 bytes addressed by lanes i/4, 4+i/4, 8+i/4, 12+i/4), each
+//                  delivering 4 consecutive keys of one head-dim column.
+//
+// Softmax.  exp2 domain with the scale folded in; the running maximum is only advanced (and O, l
+// rescaled) when it would grow by more than 2^8, which keeps exp2 arguments <= 8 and removes the
+// per-tile rescale of the 64 accumulator registers from the common path.
+//
+// Launch.  One workgroup per (query tile, query head, batch item), heaviest query tiles first.  The
+// linear workgroup id is decoded so that the G query heads that share a KV head run on the same XCD
+// (workgroup id modulo 8) back to back and stream the same K/V tiles through that XCD's L2.
 #include "apbv_common.h"
 
 namespace apbv {
@@ -29,50 +44,124 @@ constexpr int kWaves = 4;
 constexpr int kThreads = kWaves * 64;
 constexpr int kBM = 32 * kWaves;   // query rows per workgroup
 constexpr int kBN = 64;            // keys per tile
+constexpr int kXcds = 8;
+constexpr float kRescaleThreshold = 8.0f;   // log2 units
 
-__device__ __forceinline__ u32x4 ld16(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+#define APBV_LDS(T) __attribute__((address_space(3))) T*
+#define APBV_GLB(T) const __attribute__((address_space(1))) T*
 
-// Row pointer of virtual key j in one of the three segments (nullptr past the end).
-struct SegRows {
-  const bf16_t* base[3];
-  int64_t st[3];
-  int64_t l_a, n_vis, s_kv;
-  __device__ __forceinline__ const bf16_t* row(int64_t j) const {
-    if (j < l_a) return base[0] + j * st[0];
-    if (j < n_vis) return base[1] + (j - l_a) * st[1];
-    if (j < s_kv) return base[2] + (j - n_vis) * st[2];
-    return nullptr;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+template <int D>
+struct Tile {
+  static constexpr int ROW_BYTES = D * 2;
+  static constexpr int KC = D / 8;                        // 16-byte chunks per row
+  static constexpr int RPI = 1024 / ROW_BYTES;            // rows covered by one wave-wide LDS-direct load
+  static constexpr int IPW = kBN / RPI / kWaves;          // such loads per wave per tile (per tensor)
+  static constexpr int KS = D / 16;                       // MFMA k-steps over the head dimension
+  static constexpr int DB = D / 32;                       // 32-row blocks of O^T
+  static constexpr int TILE_BYTES = kBN * ROW_BYTES;
+  // chunk swizzles (functions of the row within the tile)
+  __device__ static __forceinline__ int fk(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+  __device__ static __forceinline__ int fv(int r) { return D == 128 ? ((r & 3) << 2) : (((r >> 1) & 1) << 2); }
+};
+
+struct Segs {
+  const char *b0, *b1, *b2;   // byte pointers of the three segments, already offset to (batch, kv head)
+  int64_t p0, p1, p2;         // bytes between consecutive tokens
+  int64_t e0, e1, e2;         // one past the last virtual key of each segment (starts are 0, e0, e1)
+};
+
+// Pick the fields of the segment that holds virtual key j (selects, no indexed access).
+__device__ __forceinline__ void seg_of(const Segs sg, int64_t j, const char*& base, int64_t& pitch, int64_t& start,
+                                       int64_t& end) {
+  const bool in0 = j < sg.e0, in1 = j < sg.e1;
+  base = in0 ? sg.b0 : (in1 ? sg.b1 : sg.b2);
+  pitch = in0 ? sg.p0 : (in1 ? sg.p1 : sg.p2);
+  start = in0 ? 0 : (in1 ? sg.e0 : sg.e1);
+  end = in0 ? sg.e0 : (in1 ? sg.e1 : sg.e2);
+}
+
+// Per-lane source offsets of the LDS-direct loads of one tensor, valid while the tiles stay inside one
+// segment: off[u] = row_u * pitch + 16 * swizzled_chunk_u (32-bit), so that a tile costs no vector
+// arithmetic: every load is  uniform 64-bit tile base + off[u].
+template <int D, bool kIsK>
+struct TileLoader {
+  using T = Tile<D>;
+  Segs sg;
+  int64_t s_kv;
+  int seg;                 // segment the offsets were computed for (-1: none)
+  uint32_t off[T::IPW];
+  int wave, lane;
+
+  __device__ __forceinline__ void init(const Segs& s, int64_t skv, int w, int l) {
+    sg = s;
+    s_kv = skv;
+    seg = -1;
+    wave = w;
+    lane = l;
+#pragma unroll
+    for (int u = 0; u < T::IPW; ++u) off[u] = 0;
+  }
+  __device__ __forceinline__ int row(int u) const { return (wave * T::IPW + u) * T::RPI + lane / T::KC; }
+  __device__ __forceinline__ int chunk(int u) const {
+    const int r = row(u);
+    return (lane % T::KC) ^ (kIsK ? T::fk(r) : T::fv(r));
+  }
+
+  // Issue this wave's share of the loads of the tile that starts at virtual key j0.
+  __device__ __forceinline__ void issue(int64_t j0, unsigned char* lds_tile) {
+    const char* base;
+    int64_t pitch, start, end;
+    seg_of(sg, j0, base, pitch, start, end);               // uniform
+    const int s = (j0 >= sg.e0) + (j0 >= sg.e1);
+    if (j0 + kBN <= end) {
+      if (s != seg) {                                      // entering a new segment: new pitch
+        seg = s;
+#pragma unroll
+        for (int u = 0; u < T::IPW; ++u) off[u] = (uint32_t)row(u) * (uint32_t)pitch + 16u * (uint32_t)chunk(u);
+      }
+      const char* tile_base = base + (j0 - start) * pitch;
+#pragma unroll
+      for (int u = 0; u < T::IPW; ++u)
+        __builtin_amdgcn_global_load_lds((APBV_GLB(void))(tile_base + off[u]),
+                                         (APBV_LDS(void))(lds_tile + (wave * T::IPW + u) * T::RPI * T::ROW_BYTES), 16, 0, 0);
+    } else {
+      // the tile straddles a segment boundary or the end of the keys: per-row segment lookup
+#pragma unroll
+      for (int u = 0; u < T::IPW; ++u) {
+        int64_t j = j0 + row(u);
+        j = j < s_kv ? j : s_kv - 1;                       // rows past the end repeat the last key: always masked
+        const char* bj;
+        int64_t pj, sj, ej;
+        seg_of(sg, j, bj, pj, sj, ej);
+        __builtin_amdgcn_global_load_lds((APBV_GLB(void))(bj + (j - sj) * pj + 16 * chunk(u)),
+                                         (APBV_LDS(void))(lds_tile + (wave * T::IPW + u) * T::RPI * T::ROW_BYTES), 16, 0, 0);
+      }
+    }
   }
 };
 
 template <int D>
-struct Tile {
-  static constexpr int KC = D / 8;                 // 16-byte chunks per K row
-  static constexpr int K_ROWS_PER_PASS = kThreads / KC;
-  static constexpr int K_PASSES = kBN / K_ROWS_PER_PASS;
-  static constexpr int V_ITEMS = 16 * KC;          // (key quad, dd chunk) items per tile
-  static constexpr int KS = D / 16;                // MFMA k-steps over the head dimension
-  static constexpr int DB = D / 32;                // 32-row blocks of O^T
-  static constexpr int K_BYTES = kBN * D * 2;
-  static constexpr int V_BYTES = D * kBN * 2;
-};
-
-// LDS offsets (bytes).  K tile: row `key` (D*2 bytes), chunk c of 16 bytes, swizzled by key&7.
-template <int D>
-__device__ __forceinline__ int k_lds_off(int key, int chunk) {
-  return key * (D * 2) + ((chunk ^ (key & 7)) << 4);
-}
-// V^T tile: row `dd` (128 bytes = 8 chunks), swizzled by (dd ^ dd>>3)&7.
-__device__ __forceinline__ int v_lds_off(int dd, int chunk) {
-  return dd * (kBN * 2) + ((chunk ^ ((dd ^ (dd >> 3)) & 7)) << 4);
-}
-
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles) {
+__global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles,
+                                                                     const int n_items) {
   using T = Tile<D>;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[T::K_BYTES + T::V_BYTES];
-  unsigned char* const ks = smem;
-  unsigned char* const vt = smem + T::K_BYTES;
+  __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[T::TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[T::TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[T::TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[T::TILE_BYTES];
+
+  // ---- workgroup -> (query tile, head, batch); the heads of one KV group share an XCD
+  const int xcd = blockIdx.x % kXcds;
+  const int slot = blockIdx.x / kXcds;
+  const int item = (slot / p.group) * kXcds + xcd;
+  if (item >= n_items) return;
+  const int g = slot % p.group;
+  const int bh = p.batch * p.hkv;
+  const int qt = n_qtiles - 1 - item / bh;       // heaviest query tiles first
+  const int b = (item % bh) / p.hkv;
+  const int kvh = (item % bh) % p.hkv;
+  const int h = kvh * p.group + g;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -80,90 +169,50 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   const int lq = lane & 31;       // query column / A-operand row within a 32-block
   const int hh = lane >> 5;       // lane half
 
-  // Heaviest query tiles (most visible keys) first.
-  const int qt = n_qtiles - 1 - (int)blockIdx.x;
-  const int h = blockIdx.y;
-  const int b = blockIdx.z;
-  const int kvh = h / p.group;
-
   const int64_t i0 = (int64_t)qt * kBM;                 // first query position of the workgroup
   const int64_t iw = i0 + wave * 32;                    // first query position of the wave
   const int64_t i_row = iw + lq;                        // this lane's query position
 
-  SegRows kr, vr;
-#pragma unroll
-  for (int s = 0; s < 3; ++s) {
-    kr.base[s] = p.k_seg[s].ptr + (int64_t)b * p.k_seg[s].sb + (int64_t)kvh * p.k_seg[s].sh;
-    kr.st[s] = p.k_seg[s].st;
-    vr.base[s] = p.v_seg[s].ptr + (int64_t)b * p.v_seg[s].sb + (int64_t)kvh * p.v_seg[s].sh;
-    vr.st[s] = p.v_seg[s].st;
+  Segs ks, vs;
+  {
+    auto kbase = [&](int s) {
+      return reinterpret_cast<const char*>(p.k_seg[s].ptr + (int64_t)b * p.k_seg[s].sb + (int64_t)kvh * p.k_seg[s].sh);
+    };
+    auto vbase = [&](int s) {
+      return reinterpret_cast<const char*>(p.v_seg[s].ptr + (int64_t)b * p.v_seg[s].sb + (int64_t)kvh * p.v_seg[s].sh);
+    };
+    ks.b0 = kbase(0); ks.b1 = kbase(1); ks.b2 = kbase(2);
+    vs.b0 = vbase(0); vs.b1 = vbase(1); vs.b2 = vbase(2);
+    ks.p0 = p.k_seg[0].st * 2; ks.p1 = p.k_seg[1].st * 2; ks.p2 = p.k_seg[2].st * 2;
+    vs.p0 = p.v_seg[0].st * 2; vs.p1 = p.v_seg[1].st * 2; vs.p2 = p.v_seg[2].st * 2;
+    ks.e0 = vs.e0 = p.l_a; ks.e1 = vs.e1 = p.n_vis; ks.e2 = vs.e2 = p.s_kv;
   }
-  kr.l_a = vr.l_a = p.l_a;
-  kr.n_vis = vr.n_vis = p.n_vis;
-  kr.s_kv = vr.s_kv = p.s_kv;
 
   // ---- Q^T fragments (B operand), kept in registers for the whole key loop.
   bf16x8 qf[T::KS];
   {
-    const bf16_t* qrow = p.q.ptr + (int64_t)b * p.q.sb + (int64_t)h * p.q.sh + i_row * p.q.st;
-    const bool ok = i_row < p.L;
+    const bf16_t* qrow = p.q.ptr + (int64_t)b * p.q.sb + (int64_t)h * p.q.sh + (i_row < p.L ? i_row : p.L - 1) * p.q.st;
 #pragma unroll
-    for (int s = 0; s < T::KS; ++s) {
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (ok) v = ld16(qrow + 16 * s + 8 * hh);
-      qf[s] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int s = 0; s < T::KS; ++s) qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(qrow + 16 * s + 8 * hh));
   }
 
-  // ---- staging assignment
-  const int kc = tid % T::KC;                 // K: chunk within the row
-  const int kr0 = tid / T::KC;                // K: first row handled
-  const int vdg = tid % T::KC;                // V: dd chunk (8 dd)
-  const int vkq = tid / T::KC;                // V: key quad (valid if < 16)
-  const bool v_active = vkq < 16;
-  const int v_chunk = 2 * (vkq >> 2) + (vkq & 1);
-  const int v_half = (vkq & 3) >> 1;
-
-  u32x4 kreg[T::K_PASSES];
-  u32x4 vreg[4];
-
-  auto load_tile = [&](int64_t j0) {
+  // ---- per-lane LDS read offsets
+  // K (A operand of S^T): row 32*kb + lq, chunk (2*ks + hh) ^ fk(row)
+  int k_off[T::KS];
 #pragma unroll
-    for (int s = 0; s < T::K_PASSES; ++s) {
-      const bf16_t* r = kr.row(j0 + kr0 + s * T::K_ROWS_PER_PASS);
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (r) v = ld16(r + 8 * kc);
-      kreg[s] = v;
-    }
-    if (v_active) {
+  for (int c = 0; c < T::KS; ++c) k_off[c] = lq * T::ROW_BYTES + (((2 * c + hh) ^ T::fk(lq)) << 4);
+  // V (A operand of O^T, transposing read): within a 16-lane group, source lane s addresses row s/4,
+  // head-dim columns 32*db + 16*(group%2) + 4*(s%4) .. +3
+  int v_off[T::DB];
+  {
+    const int grp = lane >> 4, sl = lane & 15;
+    const int row = 4 * (grp >> 1) + (sl >> 2);            // + 32*kb + 16*t + 8*eh as an immediate
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        const bf16_t* r = vr.row(j0 + 4 * vkq + a);
-        u32x4 v = {0u, 0u, 0u, 0u};
-        if (r) v = ld16(r + 8 * vdg);
-        vreg[a] = v;
-      }
+    for (int d = 0; d < T::DB; ++d) {
+      const int dd0 = 32 * d + 16 * (grp & 1) + 4 * (sl & 3);
+      v_off[d] = row * T::ROW_BYTES + ((((dd0 >> 3) ^ T::fv(row))) << 4) + ((dd0 & 7) >> 2) * 8;
     }
-  };
-  auto store_tile = [&]() {
-#pragma unroll
-    for (int s = 0; s < T::K_PASSES; ++s) {
-      const int row = kr0 + s * T::K_ROWS_PER_PASS;
-      *reinterpret_cast<u32x4*>(ks + k_lds_off<D>(row, kc)) = kreg[s];
-    }
-    if (v_active) {
-      // 4 keys x 8 dd in registers -> for each dd the 4 keys as one 8-byte LDS write.
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-        u32x2 w;
-        w.x = __builtin_amdgcn_perm(vreg[1][e >> 1], vreg[0][e >> 1], sel);
-        w.y = __builtin_amdgcn_perm(vreg[3][e >> 1], vreg[2][e >> 1], sel);
-        const int dd = 8 * vdg + e;
-        *reinterpret_cast<u32x2*>(vt + v_lds_off(dd, v_chunk) + 8 * v_half) = w;
-      }
-    }
-  };
+  }
 
   // ---- online softmax state (per lane: one query; the two lane halves hold disjoint key subsets)
   f32x16 o[T::DB];
@@ -171,120 +220,143 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   for (int d = 0; d < T::DB; ++d)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
-  float m_run = -INFINITY;   // running maximum of the scaled (log2-domain) logits, whole row
-  float l_run = 0.f;         // running sum of exp2, this lane half only
+  float m_ref = -INFINITY;   // reference maximum of the scaled (log2-domain) logits, whole row
+  float l_run = 0.f;         // running sum of exp2(. - m_ref), this lane half only
 
   // Keys the workgroup / this wave can see at all.
   const int64_t i_last_wg = (i0 + kBM - 1 < p.L - 1) ? i0 + kBM - 1 : p.L - 1;
-  const int64_t n_keys_wg = i_last_wg + 1 + p.n_vis;
-  const int n_tiles = (int)((n_keys_wg + kBN - 1) / kBN);
+  const int n_tiles = (int)((i_last_wg + 1 + p.n_vis + kBN - 1) / kBN);
   const int64_t j_lim_wave = iw + 31 + p.n_vis;      // last virtual key any row of the wave may see
 
-  load_tile(0);
-  store_tile();
-  __syncthreads();
-
-  for (int t = 0; t < n_tiles; ++t) {
-    const int64_t j0 = (int64_t)t * kBN;
-    if (t + 1 < n_tiles) load_tile(j0 + kBN);
-
-    if (j0 <= j_lim_wave) {
-      // ---- S^T = K Q^T for the two 32-key blocks
-      f32x16 s[2];
+  auto compute = [&](const unsigned char* kt, const unsigned char* vt, int64_t j0) {
+    if (j0 > j_lim_wave) return;
+    // ---- S^T = K Q^T for the two 32-key blocks
+    f32x16 s[2];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
 #pragma unroll
-        for (int c = 0; c < T::KS; ++c) {
-          const u32x4 a = *reinterpret_cast<const u32x4*>(ks + k_lds_off<D>(32 * kb + lq, 2 * c + hh));
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[c], s[kb], 0, 0, 0);
-        }
+      for (int c = 0; c < T::KS; ++c) {
+        const u32x4 a = *reinterpret_cast<const u32x4*>(kt + kb * 32 * T::ROW_BYTES + k_off[c]);
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[c], s[kb], 0, 0, 0);
       }
-      // ---- mask (only tiles that reach above the wave's first diagonal element)
-      if (j0 + kBN - 1 > iw + p.n_vis) {
-        const int64_t jmax = i_row + p.n_vis;        // last visible virtual key of this lane's query
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int64_t j = j0 + 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (j > jmax) s[kb][r] = -INFINITY;
-          }
-      }
-      // ---- online softmax
-      float mx = s[0][0];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx * p.scale_log2);
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-      m_run = m_new;
-      float psum = 0.f;
+    }
+    // ---- mask (only tiles that reach above the wave's first diagonal element)
+    if (j0 + kBN - 1 > iw + p.n_vis) {
+      const int jrel_max = (int)(i_row + p.n_vis - j0);   // last visible key of this lane's query, tile-relative
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], p.scale_log2, -m_new));
-          s[kb][r] = e;
-          psum += e;
+          const int jr = 32 * kb + 8 * (r >> 2) + 4 * hh + (r & 3);
+          if (jr > jrel_max) s[kb][r] = -INFINITY;
         }
-      l_run = l_run * alpha + psum;
+    }
+    // ---- online softmax with lazy rescaling
+    float mx = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+    {
+      auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
+    const float m_new = fmaxf(m_ref, mx * p.scale_log2);
+    if (__builtin_amdgcn_ballot_w64(m_new > m_ref + kRescaleThreshold) != 0) {
+      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);    // m_ref = -inf on the first tile: alpha = 0
+      m_ref = m_new;
+      l_run *= alpha;
 #pragma unroll
       for (int d = 0; d < T::DB; ++d)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
+    }
+    float psum = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], p.scale_log2, -m_ref));
+        s[kb][r] = e;
+        psum += e;
+      }
+    l_run += psum;
 
-      // ---- O^T += V^T P^T
+    // ---- O^T += V^T P^T
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-          bf16x8 pf;
+      for (int tt = 0; tt < 2; ++tt) {
+        bf16x8 pf;
 #pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            f32x2 xy = {s[kb][8 * tt + e], s[kb][8 * tt + e + 1]};
-            bf16x2 c = __builtin_convertvector(xy, bf16x2);
-            pf[e] = c[0];
-            pf[e + 1] = c[1];
-          }
-#pragma unroll
-          for (int d = 0; d < T::DB; ++d) {
-            const u32x4 a = *reinterpret_cast<const u32x4*>(vt + v_lds_off(32 * d + lq, 4 * kb + 2 * tt + hh));
-            o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf, o[d], 0, 0, 0);
-          }
+        for (int e = 0; e < 8; e += 2) {
+          f32x2 xy = {s[kb][8 * tt + e], s[kb][8 * tt + e + 1]};
+          bf16x2 c = __builtin_convertvector(xy, bf16x2);
+          pf[e] = c[0];
+          pf[e + 1] = c[1];
         }
-    }
+        const int row_off = (32 * kb + 16 * tt) * T::ROW_BYTES;
+#pragma unroll
+        for (int d = 0; d < T::DB; ++d) {
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((APBV_LDS(s16x4))(vt + row_off + v_off[d]));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((APBV_LDS(s16x4))(vt + row_off + 8 * T::ROW_BYTES + v_off[d]));
+          typedef __attribute__((ext_vector_type(8))) short s16x8;
+          const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), pf, o[d], 0, 0, 0);
+        }
+      }
+  };
 
-    __syncthreads();                 // every wave is done reading tile t
+  // ---- key loop: LDS double buffer, loads of tile t+1 in flight while tile t is computed
+  TileLoader<D, true> kld;
+  TileLoader<D, false> vld;
+  kld.init(ks, p.s_kv, wave, lane);
+  vld.init(vs, p.s_kv, wave, lane);
+  kld.issue(0, k_lds0);
+  vld.issue(0, v_lds0);
+  for (int t = 0; t < n_tiles; t += 2) {
+    const int64_t j0 = (int64_t)t * kBN;
+    __syncthreads();          // tile t has landed (all waves), and everyone is done with the other buffer
     if (t + 1 < n_tiles) {
-      store_tile();
-      __syncthreads();               // tile t+1 is visible
+      kld.issue(j0 + kBN, k_lds1);
+      vld.issue(j0 + kBN, v_lds1);
     }
+    compute(k_lds0, v_lds0, j0);
+    if (t + 1 >= n_tiles) break;
+    __syncthreads();
+    if (t + 2 < n_tiles) {
+      kld.issue(j0 + 2 * kBN, k_lds0);
+      vld.issue(j0 + 2 * kBN, v_lds0);
+    }
+    compute(k_lds1, v_lds1, j0 + kBN);
   }
 
   // ---- epilogue: normalise, round to bf16, store; optional log-sum-exp
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  float l_tot;
+  {
+    auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
+    l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+  }
   const float inv = 1.0f / l_tot;
   if (i_row < p.L) {
     bf16_t* orow = p.out + (((int64_t)b * p.L + i_row) * p.hq + h) * D;
 #pragma unroll
     for (int d = 0; d < T::DB; ++d)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f32x2 x01 = {o[d][4 * g + 0] * inv, o[d][4 * g + 1] * inv};
-        f32x2 x23 = {o[d][4 * g + 2] * inv, o[d][4 * g + 3] * inv};
+      for (int gq = 0; gq < 4; ++gq) {
+        f32x2 x01 = {o[d][4 * gq + 0] * inv, o[d][4 * gq + 1] * inv};
+        f32x2 x23 = {o[d][4 * gq + 2] * inv, o[d][4 * gq + 3] * inv};
         bf16x2 c01 = __builtin_convertvector(x01, bf16x2);
         bf16x2 c23 = __builtin_convertvector(x23, bf16x2);
         u32x2 w;
         w.x = __builtin_bit_cast(uint32_t, c01);
         w.y = __builtin_bit_cast(uint32_t, c23);
-        *reinterpret_cast<u32x2*>(orow + 32 * d + 8 * g + 4 * hh) = w;
+        *reinterpret_cast<u32x2*>(orow + 32 * d + 8 * gq + 4 * hh) = w;
       }
     if (p.lse != nullptr && hh == 0)
-      p.lse[((int64_t)b * p.hq + h) * p.L + i_row] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+      p.lse[((int64_t)b * p.hq + h) * p.L + i_row] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
   }
 }
 
@@ -292,12 +364,15 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream) {
   const int n_qtiles = (int)((p.L + kBM - 1) / kBM);
-  dim3 grid(n_qtiles, p.hq, p.batch);
+  const int64_t n_items = (int64_t)n_qtiles * p.batch * p.hkv;
+  const int64_t n_blocks = (n_items + kXcds - 1) / kXcds * kXcds * p.group;
+  if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)n_blocks);
   dim3 block(kThreads);
   if (head_dim == 128)
-    hipLaunchKernelGGL(host_attention_kernel<128>, grid, block, 0, stream, p, n_qtiles);
+    hipLaunchKernelGGL(host_attention_kernel<128>, grid, block, 0, stream, p, n_qtiles, (int)n_items);
   else if (head_dim == 64)
-    hipLaunchKernelGGL(host_attention_kernel<64>, grid, block, 0, stream, p, n_qtiles);
+    hipLaunchKernelGGL(host_attention_kernel<64>, grid, block, 0, stream, p, n_qtiles, (int)n_items);
   else
     return APBV_ERR_UNSUPPORTED;
   return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
