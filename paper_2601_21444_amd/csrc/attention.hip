@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // uniform: keeps LDS tile addresses in SGPRs
   const int lq = lane & 31;       // query column / A-operand row within a 32-block
   const int hh = lane >> 5;       // lane half
 
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[d][r] = 0.f;
   float m_ref = -INFINITY;   // reference maximum of the scaled (log2-domain) logits, whole row
-  float l_run = 0.f;         // running sum of exp2(. - m_ref), this lane half only
+  float l_run = 0.f;         // running sum of the bf16-rounded exp2(. - m_ref), this lane half only
 
   // Keys the workgroup / this wave can see at all.
   const int64_t i_last_wg = (i0 + kBM - 1 < p.L - 1) ? i0 + kBM - 1 : p.L - 1;
@@ -273,27 +273,23 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
     }
-    float psum = 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], p.scale_log2, -m_ref));
-        s[kb][r] = e;
-        psum += e;
-      }
-    l_run += psum;
+      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], p.scale_log2, -m_ref));
 
     // ---- O^T += V^T P^T
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int tt = 0; tt < 2; ++tt) {
+        // round P to bf16 (the PV operand) and add the rounded values into the row sum, two per dot2
         bf16x8 pf;
 #pragma unroll
         for (int e = 0; e < 8; e += 2) {
           f32x2 xy = {s[kb][8 * tt + e], s[kb][8 * tt + e + 1]};
           bf16x2 c = __builtin_convertvector(xy, bf16x2);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(c, bf16x2{(__bf16)1.0f, (__bf16)1.0f}, l_run, false);
           pf[e] = c[0];
           pf[e + 1] = c[1];
         }
