@@ -20,7 +20,7 @@ namespace apbv {
 namespace {
 
 constexpr int kSelectThreads = 1024;
-constexpr int64_t kLdsSortMax = 8192;          // winners that fit the LDS sort (12 bytes each)
+constexpr int64_t kLdsSortMax = 8192;          // entries that fit the LDS selection arrays (14 bytes each)
 
 __host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -32,7 +32,7 @@ inline int64_t pow2_ceil(int64_t x) {
 
 struct Workspace {
   size_t qbar_off, scores_off, sort_keys_off, sort_idx_off, total;
-  int64_t n_sort;       // padded number of sorted entries
+  int64_t n_sort;       // capacity (entries, a power of two) of the selection's sort arrays
   bool sort_in_global;
 };
 
@@ -43,14 +43,17 @@ Workspace plan_workspace(int batch, int hkv, int d, int64_t L, int64_t l_p) {
   off = align_up(off + (size_t)batch * hkv * d * sizeof(double), 256);
   w.scores_off = off;
   off = align_up(off + (size_t)batch * hkv * (size_t)L * sizeof(double), 256);
+  // capacity of the sort arrays: room for the candidates of the fast path (the winners plus the rest
+  // of the threshold bucket) when that fits the LDS, else exactly the padded winners
   w.n_sort = pow2_ceil(l_p > 1 ? l_p : 1);
   w.sort_in_global = w.n_sort > kLdsSortMax;
+  if (!w.sort_in_global && 2 * w.n_sort <= kLdsSortMax) w.n_sort *= 2;
   w.sort_keys_off = w.sort_idx_off = off;
   if (w.sort_in_global) {
     w.sort_keys_off = off;
     off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * sizeof(uint64_t), 256);
     w.sort_idx_off = off;
-    off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * sizeof(uint32_t), 256);
+    off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * (sizeof(uint32_t) + sizeof(uint16_t)), 256);
   }
   w.total = off;
   return w;
@@ -62,21 +65,45 @@ __device__ __forceinline__ double bf16_to_f64(uint32_t bits16) {
 
 // ------------------------------------------------------------------------------------------------
 // q_bar[b, v, c] = sum_g sum_t Q_qr[b, t, v*G+g, c]   (float64; the addends are bf16 so the sum is
-// exact or within an ulp whatever the order)
-__global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, int group, int d, double* qbar, int hkv) {
-  __shared__ double part[1024];
+// exact or within an ulp whatever the order).  One workgroup per (KV head, batch item): D/8 lanes per
+// probe row (16-byte loads), 1024/(D/8) rows in flight, then a shuffle + LDS reduction.
+template <int D>
+__global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, int group, double* qbar, int hkv) {
+  constexpr int KC = D / 8;
+  constexpr int R = 1024 / KC;                 // row groups
+  __shared__ double part[16][D];
   const int v = blockIdx.x, b = blockIdx.y;
-  const int c = threadIdx.x % d;
-  const int slice = threadIdx.x / d, n_slices = blockDim.x / d;
-  const bf16_t* base = q.ptr + (int64_t)b * q.sb + (int64_t)v * group * q.sh + c;
-  double acc = 0.0;
-  for (int64_t t = slice; t < n_q; t += n_slices)
-    for (int g = 0; g < group; ++g) acc += bf16_to_f64(base[t * q.st + (int64_t)g * q.sh]);
-  part[threadIdx.x] = acc;
+  const int c8 = threadIdx.x % KC, rg = threadIdx.x / KC;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bf16_t* base = q.ptr + (int64_t)b * q.sb + (int64_t)v * group * q.sh + 8 * c8;
+  double acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.0;
+  const int64_t n_rows = n_q * group;
+  for (int64_t rr = rg; rr < n_rows; rr += R) {
+    const int64_t t = rr / group, g = rr % group;
+    const u32x4 x = *reinterpret_cast<const u32x4*>(base + t * q.st + g * q.sh);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc[2 * e] += bf16_to_f64(x[e] & 0xffffu);
+      acc[2 * e + 1] += bf16_to_f64(x[e] >> 16);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+#pragma unroll
+    for (int m = KC; m < 64; m <<= 1) acc[e] += __shfl_xor(acc[e], m);
+  }
+  if (lane < KC) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) part[wave][8 * c8 + e] = acc[e];
+  }
   __syncthreads();
-  if (slice == 0) {
-    for (int s = 1; s < n_slices; ++s) acc += part[s * d + c];
-    qbar[((int64_t)b * hkv + v) * d + c] = acc;
+  if (threadIdx.x < D) {
+    double sum = 0.0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) sum += part[w][threadIdx.x];
+    qbar[((int64_t)b * hkv + v) * D + threadIdx.x] = sum;
   }
 }
 
@@ -143,137 +170,53 @@ __device__ __forceinline__ bool precedes(uint64_t ka, uint32_t ia, uint64_t kb, 
   return ka > kb || (ka == kb && ia < ib);
 }
 
-// One workgroup per (KV head, batch item).  skeys/sidx hold n_sort entries (LDS or global).
-template <bool kGlobalSort>
-__global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __restrict__ s_ws, int64_t L, int64_t l_p,
-                                                                int64_t n_sort, int32_t* __restrict__ idx_out,
-                                                                uint64_t* gkeys, uint32_t* gidx, int hkv) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
-  __shared__ uint32_t hist[256];
-  __shared__ uint64_t sh_prefix;
-  __shared__ uint32_t sh_need, sh_bucket, sh_cnt;
-  __shared__ uint32_t wave_tot[kSelectThreads / 64];
+constexpr int kBins = 2048;                    // value buckets of the fast selection path
 
-  const int v = blockIdx.x, b = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int64_t head = (int64_t)b * hkv + v;
-  const double* s = s_ws + head * L;
-  uint64_t* skeys;
-  uint32_t* sidx;
-  if (kGlobalSort) {
-    skeys = gkeys + head * n_sort;
-    sidx = gidx + head * n_sort;
-  } else {
-    skeys = reinterpret_cast<uint64_t*>(dyn);
-    sidx = reinterpret_cast<uint32_t*>(dyn + n_sort * sizeof(uint64_t));
-  }
+constexpr uint32_t kMaxBinRank = 128;          // largest bucket the rank-by-comparison step accepts
 
-  // ---- radix select, most significant byte first: after 8 passes `prefix` is the l_p-th largest key
-  // and `need` says how many keys equal to it belong to the result.
-  uint64_t prefix = 0;
-  uint32_t need = (uint32_t)l_p;
-  uint32_t bucket = 0;           // number of keys equal to the final prefix
-  for (int pass = 0; pass < 8; ++pass) {
-    const int shift = 56 - 8 * pass;
-    if (tid < 256) hist[tid] = 0;
-    __syncthreads();
-    for (int64_t j = tid; j < L; j += kSelectThreads) {
-      const uint64_t key = score_key(s[j]);
-      if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255], 1u);
-    }
-    __syncthreads();
-    if (wave == 0) {
-      // lane l owns digits 255-4l .. 252-4l (descending); find the digit holding the need-th largest
-      uint32_t c4[4], tot = 0;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        c4[q] = hist[255 - 4 * lane - q];
-        tot += c4[q];
-      }
-      uint32_t incl = tot;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
-      uint32_t excl = incl - tot;
-      if (excl < need && need <= incl) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (excl < need && need <= excl + c4[q]) {
-            sh_prefix = (prefix << 8) | (uint64_t)(255 - 4 * lane - q);
-            sh_need = need - excl;
-            sh_bucket = c4[q];
-          }
-          excl += c4[q];
-        }
-      }
-    }
-    __syncthreads();
-    prefix = sh_prefix;
-    need = sh_need;
-    bucket = sh_bucket;
-  }
-  const uint64_t kth = prefix;
-  const uint32_t n_gt = (uint32_t)l_p - need;     // keys strictly above the threshold
+struct SelectShared {
+  uint32_t hist[kBins];       // entries per bucket
+  uint32_t base[kBins];       // entries in higher buckets (output offset of the bucket)
+  uint32_t fill[kBins];       // scatter cursor per bucket
+  uint64_t prefix;
+  uint32_t need, bucket, cnt, n_cand, t_bin, max_bin;
+  uint32_t wave_tot[kSelectThreads / 64];
+  double red_lo[kSelectThreads / 64], red_hi[kSelectThreads / 64];
+};
 
-  // ---- collect the winners (unordered above the threshold; ties at the threshold by index)
-  if (tid == 0) sh_cnt = 0;
-  for (int64_t i = l_p + tid; i < n_sort; i += kSelectThreads) {   // padding sorts last
-    skeys[i] = 0;
-    sidx[i] = 0xffffffffu;
+// Inclusive scan of one value per thread over the whole workgroup (1024 threads); returns the
+// inclusive prefix, *total gets the workgroup sum.
+__device__ __forceinline__ uint32_t block_scan_incl(uint32_t x, SelectShared& sh, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t incl = x;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off);
+    if (lane >= off) incl += o;
   }
+  __syncthreads();                      // wave_tot may still be read from a previous use
+  if (lane == 63) sh.wave_tot[wave] = incl;
   __syncthreads();
-  if (bucket == need) {
-    // every key equal to the threshold is taken: no ordering constraint while collecting
-    for (int64_t j = tid; j < L; j += kSelectThreads) {
-      const uint64_t key = score_key(s[j]);
-      if (key >= kth) {
-        const uint32_t pos = atomicAdd(&sh_cnt, 1u);
-        skeys[pos] = key;
-        sidx[pos] = (uint32_t)j;
-      }
-    }
-  } else {
-    // more equal keys than needed: take the `need` lowest indices.  Each thread scans a contiguous
-    // index range; an exclusive scan of the per-thread tie counts gives each tie its rank by index.
-    const int64_t chunk = (L + kSelectThreads - 1) / kSelectThreads;
-    const int64_t lo = (int64_t)tid * chunk, hi = (lo + chunk < L) ? lo + chunk : L;
-    uint32_t n_eq = 0;
-    for (int64_t j = lo; j < hi; ++j) n_eq += (score_key(s[j]) == kth);
-    uint32_t incl = n_eq;
+  uint32_t base = 0, tot = 0;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const uint32_t o = __shfl_up(incl, off);
-      if (lane >= off) incl += o;
-    }
-    if (lane == 63) wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t rank = incl - n_eq;
-    for (int w = 0; w < wave; ++w) rank += wave_tot[w];
-    for (int64_t j = lo; j < hi; ++j) {
-      const uint64_t key = score_key(s[j]);
-      if (key > kth) {
-        const uint32_t pos = atomicAdd(&sh_cnt, 1u);
-        skeys[pos] = key;
-        sidx[pos] = (uint32_t)j;
-      } else if (key == kth) {
-        if (rank < need) {
-          skeys[n_gt + rank] = key;
-          sidx[n_gt + rank] = (uint32_t)j;
-        }
-        ++rank;
-      }
-    }
+  for (int w = 0; w < kSelectThreads / 64; ++w) {
+    const uint32_t t = sh.wave_tot[w];
+    if (w < wave) base += t;
+    tot += t;
   }
-  __syncthreads();
+  *total = tot;
+  return incl + base;
+}
 
-  // ---- bitonic sort of n_sort entries into (key descending, index ascending) order
-  for (int64_t k = 2; k <= n_sort; k <<= 1) {
-    for (int64_t j = k >> 1; j > 0; j >>= 1) {
-      for (int64_t pidx = tid; pidx < (n_sort >> 1); pidx += kSelectThreads) {
-        const int64_t i = ((pidx / j) * 2 * j) + (pidx % j);
-        const int64_t q = i + j;
+// Bitonic sort of n_sort (a power of two) entries into (key descending, index ascending) order.
+__device__ __forceinline__ void bitonic_sort(uint64_t* skeys, uint32_t* sidx, int64_t n_sort64) {
+  const uint32_t tid = threadIdx.x;
+  const uint32_t n_sort = (uint32_t)n_sort64, half = n_sort >> 1;
+  for (uint32_t k = 2; k <= n_sort; k <<= 1) {
+    for (uint32_t j = k >> 1, lj = 31 - __builtin_clz(j); j > 0; j >>= 1, --lj) {
+      for (uint32_t pidx = tid; pidx < half; pidx += kSelectThreads) {
+        const uint32_t i = ((pidx >> lj) << (lj + 1)) | (pidx & (j - 1));
+        const uint32_t q = i + j;
         const bool up = (i & k) == 0;          // this run is sorted "first precedes"
         const uint64_t ka = skeys[i], kb = skeys[q];
         const uint32_t ia = sidx[i], ib = sidx[q];
@@ -288,6 +231,256 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __
       __syncthreads();
     }
   }
+}
+
+// Fast path: a bucket sort by VALUE.  A monotone map sends every score to one of kBins equal-width
+// buckets between the minimum and the maximum score.  A suffix scan of the bucket counts gives each
+// bucket its output offset and finds the bucket that holds the l_p-th largest score; the entries of
+// that bucket and of all higher ones are scattered into bucket-grouped order, and each entry then finds
+// its rank inside its (small) bucket by direct comparison.  Because the map is monotone, bucket order
+// followed by (key descending, index ascending) inside a bucket is the global order, ties included.
+// Returns false (nothing written) if the candidates do not fit `cap` or a bucket is too crowded to rank
+// by comparison; the caller then takes the exact radix path.
+__device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s, int64_t L, int64_t l_p, int64_t cap,
+                                                   uint64_t* skeys, uint32_t* sidx, uint16_t* sbin,
+                                                   int32_t* __restrict__ idx_out, SelectShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int kPer = 16;                                   // scores kept in registers per thread
+  const bool resident = L <= (int64_t)kPer * kSelectThreads;
+  double sc[kPer];
+  if (resident) {
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int64_t j = tid + (int64_t)u * kSelectThreads;
+      sc[u] = j < L ? s[j] : 0.0;
+    }
+  }
+  // apply f(j, score) to every element this thread owns
+  auto for_each = [&](auto&& f) {
+    if (resident) {
+#pragma unroll
+      for (int u = 0; u < kPer; ++u) {
+        const int64_t j = tid + (int64_t)u * kSelectThreads;
+        if (j < L) f(j, sc[u]);
+      }
+    } else {
+      for (int64_t j = tid; j < L; j += kSelectThreads) f(j, s[j]);
+    }
+  };
+  // minimum and maximum
+  double lo = INFINITY, hi = -INFINITY;
+  for_each([&](int64_t, double x) {
+    lo = fmin(lo, x);
+    hi = fmax(hi, x);
+  });
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) {
+    lo = fmin(lo, __shfl_xor(lo, m));
+    hi = fmax(hi, __shfl_xor(hi, m));
+  }
+  if (lane == 0) {
+    sh.red_lo[wave] = lo;
+    sh.red_hi[wave] = hi;
+  }
+  for (int i = tid; i < kBins; i += kSelectThreads) {
+    sh.hist[i] = 0;
+    sh.fill[i] = 0;
+  }
+  if (tid == 0) sh.max_bin = 0;
+  __syncthreads();
+#pragma unroll
+  for (int w = 0; w < kSelectThreads / 64; ++w) {
+    lo = fmin(lo, sh.red_lo[w]);
+    hi = fmax(hi, sh.red_hi[w]);
+  }
+  const double inv = (double)kBins / (hi - lo);
+  if (!(inv > 0.0) || !(inv < 1.0e300)) return false;        // all scores equal (or range overflow)
+  auto bin_of = [&](double x) {
+    int b = (int)((x - lo) * inv);
+    return b > kBins - 1 ? kBins - 1 : b;
+  };
+  for_each([&](int64_t, double x) { atomicAdd(&sh.hist[bin_of(x)], 1u); });
+  __syncthreads();
+  // thread t owns buckets kBins-1-2t and kBins-2-2t (descending): suffix counts by an inclusive scan
+  const int b0 = kBins - 1 - 2 * tid, b1 = kBins - 2 - 2 * tid;
+  const uint32_t c0 = sh.hist[b0], c1 = sh.hist[b1];
+  uint32_t total;
+  const uint32_t incl = block_scan_incl(c0 + c1, sh, &total);
+  const uint32_t excl = incl - (c0 + c1);
+  sh.base[b0] = excl;
+  sh.base[b1] = excl + c0;
+  if (excl < (uint32_t)l_p && (uint32_t)l_p <= incl) {
+    const bool first = (uint32_t)l_p <= excl + c0;
+    sh.t_bin = first ? b0 : b1;
+    sh.n_cand = first ? excl + c0 : incl;
+  }
+  __syncthreads();
+  const uint32_t n_cand = sh.n_cand;
+  const int t_bin = (int)sh.t_bin;
+  {
+    uint32_t mc = (b0 >= t_bin ? c0 : 0u);
+    mc = (b1 >= t_bin && c1 > mc) ? c1 : mc;
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) {
+      const uint32_t o = __shfl_xor(mc, m);
+      mc = o > mc ? o : mc;
+    }
+    if (lane == 0) atomicMax(&sh.max_bin, mc);
+  }
+  __syncthreads();
+  if ((int64_t)n_cand > cap || sh.max_bin > kMaxBinRank) return false;
+  // scatter the candidates into bucket-grouped order
+  for_each([&](int64_t j, double x) {
+    const int b = bin_of(x);
+    if (b >= t_bin) {
+      const uint32_t pos = sh.base[b] + atomicAdd(&sh.fill[b], 1u);
+      skeys[pos] = score_key(x);
+      sidx[pos] = (uint32_t)j;
+      sbin[pos] = (uint16_t)b;
+    }
+  });
+  __syncthreads();
+  // rank inside the bucket, write the index at its final position
+  const int64_t out_base = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * l_p;
+  for (uint32_t pos = tid; pos < n_cand; pos += kSelectThreads) {
+    const uint32_t b = sbin[pos];
+    const uint32_t first = sh.base[b], cnt = sh.hist[b];
+    const uint64_t key = skeys[pos];
+    const uint32_t idx = sidx[pos];
+    uint32_t rank = 0;
+    for (uint32_t q = first; q < first + cnt; ++q) rank += precedes(skeys[q], sidx[q], key, idx) ? 1u : 0u;
+    if (first + rank < (uint32_t)l_p) idx_out[out_base + first + rank] = (int32_t)idx;
+  }
+  return true;
+}
+
+// Exact path for any input: radix select of the l_p-th largest key, most significant byte first, then
+// collection of the l_p winners (ties at the threshold by ascending index).
+__device__ __forceinline__ void radix_collect(const double* __restrict__ s, int64_t L, int64_t l_p, uint64_t* skeys,
+                                              uint32_t* sidx, SelectShared& sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // after 8 passes `prefix` is the l_p-th largest key and `need` says how many keys equal to it belong
+  // to the result
+  uint64_t prefix = 0;
+  uint32_t need = (uint32_t)l_p;
+  uint32_t bucket = 0;           // number of keys equal to the final prefix
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+    __syncthreads();
+    if (tid < 256) sh.hist[tid] = 0;
+    __syncthreads();
+    for (int64_t j = tid; j < L; j += kSelectThreads) {
+      const uint64_t key = score_key(s[j]);
+      if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&sh.hist[(key >> shift) & 255], 1u);
+    }
+    __syncthreads();
+    if (wave == 0) {
+      // lane l owns digits 255-4l .. 252-4l (descending); find the digit holding the need-th largest
+      uint32_t c4[4], tot = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        c4[q] = sh.hist[255 - 4 * lane - q];
+        tot += c4[q];
+      }
+      uint32_t incl = tot;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+      }
+      uint32_t excl = incl - tot;
+      if (excl < need && need <= incl) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (excl < need && need <= excl + c4[q]) {
+            sh.prefix = (prefix << 8) | (uint64_t)(255 - 4 * lane - q);
+            sh.need = need - excl;
+            sh.bucket = c4[q];
+          }
+          excl += c4[q];
+        }
+      }
+    }
+    __syncthreads();
+    prefix = sh.prefix;
+    need = sh.need;
+    bucket = sh.bucket;
+  }
+  const uint64_t kth = prefix;
+  const uint32_t n_gt = (uint32_t)l_p - need;     // keys strictly above the threshold
+
+  if (tid == 0) sh.cnt = 0;
+  __syncthreads();
+  if (bucket == need) {
+    // every key equal to the threshold is taken: no ordering constraint while collecting
+    for (int64_t j = tid; j < L; j += kSelectThreads) {
+      const uint64_t key = score_key(s[j]);
+      if (key >= kth) {
+        const uint32_t pos = atomicAdd(&sh.cnt, 1u);
+        skeys[pos] = key;
+        sidx[pos] = (uint32_t)j;
+      }
+    }
+  } else {
+    // more equal keys than needed: take the `need` lowest indices.  Each thread scans a contiguous
+    // index range; an exclusive scan of the per-thread tie counts gives each tie its rank by index.
+    const int64_t chunk = (L + kSelectThreads - 1) / kSelectThreads;
+    const int64_t lo = (int64_t)tid * chunk, hi = (lo + chunk < L) ? lo + chunk : L;
+    uint32_t n_eq = 0;
+    for (int64_t j = lo; j < hi; ++j) n_eq += (score_key(s[j]) == kth);
+    uint32_t total;
+    uint32_t rank = block_scan_incl(n_eq, sh, &total) - n_eq;
+    for (int64_t j = lo; j < hi; ++j) {
+      const uint64_t key = score_key(s[j]);
+      if (key > kth) {
+        const uint32_t pos = atomicAdd(&sh.cnt, 1u);
+        skeys[pos] = key;
+        sidx[pos] = (uint32_t)j;
+      } else if (key == kth) {
+        if (rank < need) {
+          skeys[n_gt + rank] = key;
+          sidx[n_gt + rank] = (uint32_t)j;
+        }
+        ++rank;
+      }
+    }
+  }
+}
+
+// One workgroup per (KV head, batch item).  skeys/sidx hold `cap` entries (LDS or global).
+template <bool kGlobalSort>
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(const double* __restrict__ s_ws, int64_t L, int64_t l_p,
+                                                                int64_t cap, int32_t* __restrict__ idx_out,
+                                                                uint64_t* gkeys, uint32_t* gidx, int hkv) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
+  __shared__ SelectShared sh;
+
+  const int v = blockIdx.x, b = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int64_t head = (int64_t)b * hkv + v;
+  const double* s = s_ws + head * L;
+  uint64_t* skeys;
+  uint32_t* sidx;
+  if (kGlobalSort) {
+    skeys = gkeys + head * cap;
+    sidx = reinterpret_cast<uint32_t*>(reinterpret_cast<unsigned char*>(gidx) + head * cap * 6);   // [cap] u32 + [cap] u16
+  } else {
+    skeys = reinterpret_cast<uint64_t*>(dyn);
+    sidx = reinterpret_cast<uint32_t*>(dyn + cap * sizeof(uint64_t));
+  }
+
+  uint16_t* sbin = reinterpret_cast<uint16_t*>(sidx + cap);
+  if (bucket_rank_select(s, L, l_p, cap, skeys, sidx, sbin, idx_out, sh)) return;
+  radix_collect(s, L, l_p, skeys, sidx, sh);
+  int64_t n_sort = 1;
+  while (n_sort < l_p) n_sort <<= 1;
+  __syncthreads();
+  for (int64_t i = l_p + tid; i < n_sort; i += kSelectThreads) {   // padding sorts last
+    skeys[i] = 0;
+    sidx[i] = 0xffffffffu;
+  }
+  __syncthreads();
+  bitonic_sort(skeys, sidx, n_sort);
   for (int64_t i = tid; i < l_p; i += kSelectThreads) idx_out[head * l_p + i] = (int32_t)sidx[i];
 }
 
@@ -331,9 +524,12 @@ apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
 
   // pooled query
   {
-    int threads = 1024;   // a multiple of d for d in {64, 128}
-    hipLaunchKernelGGL(pool_query_kernel, dim3(p.hkv, p.batch), dim3(threads), 0, stream, p.q_probe, p.q_probe.tokens,
-                       p.group, p.d, qbar, p.hkv);
+    if (p.d == 128)
+      hipLaunchKernelGGL(pool_query_kernel<128>, dim3(p.hkv, p.batch), dim3(1024), 0, stream, p.q_probe, p.q_probe.tokens,
+                         p.group, qbar, p.hkv);
+    else
+      hipLaunchKernelGGL(pool_query_kernel<64>, dim3(p.hkv, p.batch), dim3(1024), 0, stream, p.q_probe, p.q_probe.tokens,
+                         p.group, qbar, p.hkv);
   }
   // scores
   {
@@ -354,9 +550,9 @@ apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
     } else {
       std::call_once(g_attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsSortMax * 12));
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsSortMax * 14));
       });
-      const size_t dyn = (size_t)w.n_sort * 12;
+      const size_t dyn = (size_t)w.n_sort * 14;
       hipLaunchKernelGGL(select_kernel<false>, dim3(p.hkv, p.batch), dim3(kSelectThreads), dyn, stream, scores, p.L, p.l_p,
                          w.n_sort, p.idx_out, nullptr, nullptr, p.hkv);
     }

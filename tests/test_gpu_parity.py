@@ -121,6 +121,25 @@ def test_compress_all_equal_scores_and_signed_zero():
     assert idx_r[0].tolist() == list(range(10))
 
 
+def test_compress_heavy_duplicates_force_the_exact_radix_path():
+    """8000 copies of one key row hold the cut: the value-bucket fast path cannot fit its candidates and the
+    radix path must break the tie by index; a second case puts the cut just above the cluster."""
+    for l_p, n_hot in ((100, 30), (100, 300)):
+        cfg = wl.custom("dups", (41, n_hot), 4, 2, 128, 8, 0, 0, 0, l_p, 9000)
+
+        def tamper(x, n_hot=n_hot):
+            rng = np.random.default_rng(n_hot)
+            keep = rng.choice(9000, size=n_hot, replace=False)         # rows that stay random
+            _, _, _, s = oracle.compress_kv(x.q_probe, x.k, x.v, 1)
+            for h in range(2):
+                src = int(np.argsort(s[h])[4500])                        # a median-score row
+                row = x.k[src, h].copy()
+                mask = np.ones(9000, dtype=bool)
+                mask[keep] = False
+                x.k[mask, h] = row
+        check_compress(cfg, tamper=tamper)
+
+
 def test_compress_batched_and_strided_views():
     cfg = wl.custom("b", 12, 8, 2, 128, 16, 0, 0, 0, 100, 1500)
     xs = [wl.generate(wl.custom("b", (12, i), 8, 2, 128, 16, 0, 0, 0, 100, 1500)) for i in range(3)]
