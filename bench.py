@@ -33,7 +33,7 @@ PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E, published
 # HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # each scaled by the same counter's reading for a copy kernel of known size; see profiles/.  None until
 # measured.
-MEASURED_TRAFFIC_BYTES = None
+MEASURED_TRAFFIC_BYTES = (203847 * 2 + 65536) * 1024   # profiles/host_attention_3b-128k_pmc.txt
 
 
 def parse_args():
@@ -45,6 +45,10 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compress-roofline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows the oracle is timed on")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--compress-batch", type=int, default=96,
+                    help="batch of the HBM-bound compression measurement (working set far beyond the 256 MB cache)")
     return ap.parse_args()
 
 
@@ -158,17 +162,24 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES},
     }
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_compress_roofline:
-        result["roofline_compress"] = compress_roofline(apbv, torch, cfg, q_probe, k, v)
+        result["roofline_compress"] = compress_roofline(apbv, torch, cfg, q_probe, k, v, args.compress_batch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(np, x, cfg, scale, args.cpu_rows)
     print(json.dumps(result), flush=True)
 
 
-def compress_roofline(apbv, torch, cfg, q_probe, k, v):
+def compress_roofline(apbv, torch, cfg, q_probe, k, v, batch):
     """Compression at a batch whose rotating working set exceeds the 256 MB last-level cache, so the
     K stream really comes from HBM: two buffer sets of `batch` copies each, alternated."""
-    batch = 48
     sets = []
     for s in range(2):
         kb = k.unsqueeze(0).repeat(batch, 1, 1, 1)
