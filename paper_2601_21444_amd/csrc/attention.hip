@@ -82,63 +82,98 @@ __device__ __forceinline__ void seg_of(const Segs sg, int64_t j, const char*& ba
   end = in0 ? sg.e0 : (in1 ? sg.e1 : sg.e2);
 }
 
-// Per-lane source offsets of the LDS-direct loads of one tensor, valid while the tiles stay inside one
-// segment: off[u] = row_u * pitch + 16 * swizzled_chunk_u (32-bit), so that a tile costs no vector
-// arithmetic: every load is  uniform 64-bit tile base + off[u].
-template <int D, bool kIsK>
-struct TileLoader {
+// LDS-direct 16-byte load: lane l's bytes land at lds_dst + 16*l (lds_dst uniform, in M0).  Issued through
+// inline assembly so that the kernel, not the compiler's wait-count insertion, orders these loads against
+// the LDS reads (one s_waitcnt vmcnt + barrier per tile).
+__device__ __forceinline__ void dma16_uniform(const char* base_uniform, uint32_t lane_off, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(lane_off), "s"(base_uniform)
+               : "memory");
+}
+__device__ __forceinline__ void dma16_lane(const char* addr, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_dst), "v"(addr) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_addr(const unsigned char* p) { return (uint32_t)(size_t)(APBV_LDS(const unsigned char))p; }
+
+// Sequential producer of the K and V tiles of the virtual key axis.  While consecutive tiles stay inside
+// one segment ("run") a tile costs two 64-bit scalar adds and its loads are  uniform tile base + a per-lane
+// 32-bit offset computed once per run; the tile that straddles a segment boundary (or the end of the keys)
+// takes a per-row lookup.
+template <int D>
+struct TileStream {
   using T = Tile<D>;
-  Segs sg;
+  Segs ks, vs;             // e0/e1/e2 are shared
   int64_t s_kv;
-  int seg;                 // segment the offsets were computed for (-1: none)
-  uint32_t off[T::IPW];
+  int t_next;              // next tile to issue
+  int run_end;             // tiles [t_next, run_end) lie inside one segment; kb/vb point at tile t_next
+  const char *kb, *vb;
+  int64_t kstep, vstep;    // kBN * pitch
+  uint32_t koff[T::IPW], voff[T::IPW];
   int wave, lane;
 
-  __device__ __forceinline__ void init(const Segs& s, int64_t skv, int w, int l) {
-    sg = s;
+  __device__ __forceinline__ int row(int u) const { return (wave * T::IPW + u) * T::RPI + lane / T::KC; }
+  __device__ __forceinline__ uint32_t ldst(int u) const { return (uint32_t)((wave * T::IPW + u) * T::RPI * T::ROW_BYTES); }
+
+  __device__ __forceinline__ void init(const Segs& k, const Segs& v, int64_t skv, int w, int l) {
+    ks = k;
+    vs = v;
     s_kv = skv;
-    seg = -1;
     wave = w;
     lane = l;
+    t_next = 0;
+    run_end = 0;
+    kb = vb = nullptr;
+    kstep = vstep = 0;
 #pragma unroll
-    for (int u = 0; u < T::IPW; ++u) off[u] = 0;
-  }
-  __device__ __forceinline__ int row(int u) const { return (wave * T::IPW + u) * T::RPI + lane / T::KC; }
-  __device__ __forceinline__ int chunk(int u) const {
-    const int r = row(u);
-    return (lane % T::KC) ^ (kIsK ? T::fk(r) : T::fv(r));
+    for (int u = 0; u < T::IPW; ++u) koff[u] = voff[u] = 0;
   }
 
-  // Issue this wave's share of the loads of the tile that starts at virtual key j0.
-  __device__ __forceinline__ void issue(int64_t j0, unsigned char* lds_tile) {
-    const char* base;
-    int64_t pitch, start, end;
-    seg_of(sg, j0, base, pitch, start, end);               // uniform
-    const int s = (j0 >= sg.e0) + (j0 >= sg.e1);
-    if (j0 + kBN <= end) {
-      if (s != seg) {                                      // entering a new segment: new pitch
-        seg = s;
+  // Start a run at tile t_next if that tile lies inside one segment.
+  __device__ __forceinline__ void start_run() {
+    const int64_t j0 = (int64_t)t_next * kBN;
+    const char *kbase, *vbase;
+    int64_t kp, vp, start, end, dummy0, dummy1;
+    seg_of(ks, j0, kbase, kp, start, end);
+    seg_of(vs, j0, vbase, vp, dummy0, dummy1);
+    if (j0 + kBN > end) return;                      // straddling tile: run stays empty
+    run_end = (int)(end / kBN);
+    kb = kbase + (j0 - start) * kp;
+    vb = vbase + (j0 - start) * vp;
+    kstep = kBN * kp;
+    vstep = kBN * vp;
 #pragma unroll
-        for (int u = 0; u < T::IPW; ++u) off[u] = (uint32_t)row(u) * (uint32_t)pitch + 16u * (uint32_t)chunk(u);
-      }
-      const char* tile_base = base + (j0 - start) * pitch;
+    for (int u = 0; u < T::IPW; ++u) {
+      const int r = row(u);
+      koff[u] = (uint32_t)r * (uint32_t)kp + 16u * (uint32_t)((lane % T::KC) ^ T::fk(r));
+      voff[u] = (uint32_t)r * (uint32_t)vp + 16u * (uint32_t)((lane % T::KC) ^ T::fv(r));
+    }
+  }
+
+  // Issue this wave's share of the loads of tile t_next into the LDS tiles at k_dst / v_dst.
+  __device__ __forceinline__ void issue(uint32_t k_dst, uint32_t v_dst) {
+    if (t_next >= run_end) start_run();
+    if (t_next < run_end) {
 #pragma unroll
-      for (int u = 0; u < T::IPW; ++u)
-        __builtin_amdgcn_global_load_lds((APBV_GLB(void))(tile_base + off[u]),
-                                         (APBV_LDS(void))(lds_tile + (wave * T::IPW + u) * T::RPI * T::ROW_BYTES), 16, 0, 0);
+      for (int u = 0; u < T::IPW; ++u) dma16_uniform(kb, koff[u], k_dst + ldst(u));
+#pragma unroll
+      for (int u = 0; u < T::IPW; ++u) dma16_uniform(vb, voff[u], v_dst + ldst(u));
+      kb += kstep;
+      vb += vstep;
     } else {
-      // the tile straddles a segment boundary or the end of the keys: per-row segment lookup
+      const int64_t j0 = (int64_t)t_next * kBN;
 #pragma unroll
       for (int u = 0; u < T::IPW; ++u) {
-        int64_t j = j0 + row(u);
-        j = j < s_kv ? j : s_kv - 1;                       // rows past the end repeat the last key: always masked
-        const char* bj;
-        int64_t pj, sj, ej;
-        seg_of(sg, j, bj, pj, sj, ej);
-        __builtin_amdgcn_global_load_lds((APBV_GLB(void))(bj + (j - sj) * pj + 16 * chunk(u)),
-                                         (APBV_LDS(void))(lds_tile + (wave * T::IPW + u) * T::RPI * T::ROW_BYTES), 16, 0, 0);
+        const int r = row(u);
+        int64_t j = j0 + r;
+        j = j < s_kv ? j : s_kv - 1;                 // rows past the end repeat the last key: always masked
+        const char *bk, *bv;
+        int64_t pk, pv, sj, ej, d0, d1;
+        seg_of(ks, j, bk, pk, sj, ej);
+        seg_of(vs, j, bv, pv, d0, d1);
+        dma16_lane(bk + (j - sj) * pk + 16 * ((lane % T::KC) ^ T::fk(r)), k_dst + ldst(u));
+        dma16_lane(bv + (j - sj) * pv + 16 * ((lane % T::KC) ^ T::fv(r)), v_dst + ldst(u));
       }
     }
+    ++t_next;
   }
 };
 
@@ -226,10 +261,12 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   // Keys the workgroup / this wave can see at all.
   const int64_t i_last_wg = (i0 + kBM - 1 < p.L - 1) ? i0 + kBM - 1 : p.L - 1;
   const int n_tiles = (int)((i_last_wg + 1 + p.n_vis + kBN - 1) / kBN);
-  const int64_t j_lim_wave = iw + 31 + p.n_vis;      // last virtual key any row of the wave may see
+  const int t_last_wave = (int)((iw + 31 + p.n_vis) / kBN);   // last tile any row of the wave can see into
+  const int t_mask_wave = (int)((iw + p.n_vis + 1) / kBN);    // first tile that reaches above the wave's diagonal
+  const int jrel0 = (int)(i_row + p.n_vis);                   // last visible virtual key of this lane's query
 
-  auto compute = [&](const unsigned char* kt, const unsigned char* vt, int64_t j0) {
-    if (j0 > j_lim_wave) return;
+  auto compute = [&](const unsigned char* kt, const unsigned char* vt, int t) {
+    if (t > t_last_wave) return;
     // ---- S^T = K Q^T for the two 32-key blocks
     f32x16 s[2];
 #pragma unroll
@@ -243,8 +280,8 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
       }
     }
     // ---- mask (only tiles that reach above the wave's first diagonal element)
-    if (j0 + kBN - 1 > iw + p.n_vis) {
-      const int jrel_max = (int)(i_row + p.n_vis - j0);   // last visible key of this lane's query, tile-relative
+    if (t >= t_mask_wave) {
+      const int jrel_max = jrel0 - t * kBN;          // last visible key of this lane's query, tile-relative
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -305,28 +342,24 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
       }
   };
 
-  // ---- key loop: LDS double buffer, loads of tile t+1 in flight while tile t is computed
-  TileLoader<D, true> kld;
-  TileLoader<D, false> vld;
-  kld.init(ks, p.s_kv, wave, lane);
-  vld.init(vs, p.s_kv, wave, lane);
-  kld.issue(0, k_lds0);
-  vld.issue(0, v_lds0);
+  // ---- key loop: LDS double buffer, the loads of tile t+1 in flight while tile t is computed
+  TileStream<D> ts;
+  ts.init(ks, vs, p.s_kv, wave, lane);
+  const uint32_t k0 = lds_addr(k_lds0), k1 = lds_addr(k_lds1), v0 = lds_addr(v_lds0), v1 = lds_addr(v_lds1);
+  // The Q fragments are in (vmcnt 0, other counters untouched): from here on only tile loads are
+  // outstanding, and the compiler knows it need not wait for vector memory inside the loop.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  ts.issue(k0, v0);
   for (int t = 0; t < n_tiles; t += 2) {
-    const int64_t j0 = (int64_t)t * kBN;
-    __syncthreads();          // tile t has landed (all waves), and everyone is done with the other buffer
-    if (t + 1 < n_tiles) {
-      kld.issue(j0 + kBN, k_lds1);
-      vld.issue(j0 + kBN, v_lds1);
-    }
-    compute(k_lds0, v_lds0, j0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of tile t has landed
+    __syncthreads();                                  // ... everyone's has, and everyone is done with the other buffer
+    if (t + 1 < n_tiles) ts.issue(k1, v1);
+    compute(k_lds0, v_lds0, t);
     if (t + 1 >= n_tiles) break;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (t + 2 < n_tiles) {
-      kld.issue(j0 + 2 * kBN, k_lds0);
-      vld.issue(j0 + 2 * kBN, v_lds0);
-    }
-    compute(k_lds1, v_lds1, j0 + kBN);
+    if (t + 2 < n_tiles) ts.issue(k0, v0);
+    compute(k_lds1, v_lds1, t + 1);
   }
 
   // ---- epilogue: normalise, round to bf16, store; optional log-sum-exp
