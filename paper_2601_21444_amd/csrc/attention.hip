@@ -7,8 +7,8 @@
 // n_vis).  Key tiles that lie entirely above that diagonal are never visited, and only tiles that
 // touch it pay for the comparison.
 //
-// Tiling.  A workgroup of 4 waves owns 128 consecutive query positions of one query head; each wave
-// owns 32 of them.  Key tiles of 64 virtual keys are copied global -> LDS by the LDS-direct load
+// Tiling.  A workgroup of 8 waves (two per SIMD, one workgroup per CU) owns 256 consecutive query
+// positions of one query head; each wave owns 32 of them.  Key tiles of 64 virtual keys are copied global -> LDS by the LDS-direct load
 // (global_load_lds_dwordx4: no VGPR staging, no VALU work), double buffered, one barrier per tile.
 // Both K and V are stored row-major [64][D] with an XOR swizzle of their 16-byte chunks; the swizzle is
 // applied on the global side (which chunk a lane fetches), because an LDS-direct load always writes
@@ -40,7 +40,7 @@
 namespace apbv {
 namespace {
 
-constexpr int kWaves = 4;
+constexpr int kWaves = 8;
 constexpr int kThreads = kWaves * 64;
 constexpr int kBM = 32 * kWaves;   // query rows per workgroup
 constexpr int kBN = 64;            // keys per tile
