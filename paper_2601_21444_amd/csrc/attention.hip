@@ -267,17 +267,39 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 
   auto compute = [&](const unsigned char* kt, const unsigned char* vt, int t) {
     if (t > t_last_wave) return;
-    // ---- S^T = K Q^T for the two 32-key blocks
+    // ---- S^T = K Q^T for the two 32-key blocks.  K fragments are read kReadAhead k-steps ahead of the MFMA
+    // that consumes them, and the order is pinned (the scheduler would otherwise sink every read next to its
+    // use to save registers, exposing the LDS latency once per MFMA).
     f32x16 s[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+    {
+      constexpr int kReadAhead = 4;
+      u32x4 ka[kReadAhead][2];
+#pragma unroll
+      for (int c = 0; c < kReadAhead; ++c)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+          ka[c][kb] = *reinterpret_cast<const u32x4*>(kt + kb * 32 * T::ROW_BYTES + k_off[c]);
 #pragma unroll
       for (int c = 0; c < T::KS; ++c) {
-        const u32x4 a = *reinterpret_cast<const u32x4*>(kt + kb * 32 * T::ROW_BYTES + k_off[c]);
-        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), qf[c], s[kb], 0, 0, 0);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[c % kReadAhead][kb]), qf[c], s[kb], 0, 0, 0);
+          if (c + kReadAhead < T::KS)
+            ka[c % kReadAhead][kb] = *reinterpret_cast<const u32x4*>(kt + kb * 32 * T::ROW_BYTES + k_off[c + kReadAhead]);
+        }
       }
+      // scheduling groups: 2*kReadAhead LDS reads, then (MFMA, LDS read) pairs, then the remaining MFMAs
+      __builtin_amdgcn_sched_group_barrier(0x100, 2 * kReadAhead, 0);
+#pragma unroll
+      for (int i = 0; i < 2 * (T::KS - kReadAhead); ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(0x008, 2 * kReadAhead, 0);
     }
     // ---- mask (only tiles that reach above the wave's first diagonal element)
     if (t >= t_mask_wave) {
