@@ -43,7 +43,8 @@ typedef enum {
 } apbv_status;
 
 /* A [tokens, heads, head_dim] bf16 view.  head_dim is contiguous (stride 1); all strides are in
- * ELEMENTS and must be multiples of 8 (16-byte vector access); ptr must be 16-byte aligned.
+ * ELEMENTS and must be multiples of 8 (16-byte vector access); stride_token must be below 2^24;
+ * ptr must be 16-byte aligned.
  * ptr may be NULL iff tokens == 0.  stride_batch is ignored when batch == 1. */
 typedef struct {
   const void* ptr;

@@ -19,6 +19,7 @@ apbv_status check_view(const apbv_tensor& t, int heads, int d, int batch, bool m
   if (t.ptr == nullptr) return APBV_ERR_NULL;
   if (!aligned(t.ptr, 16)) return APBV_ERR_SHAPE;
   if (t.stride_token < d || t.stride_token % 8) return APBV_ERR_SHAPE;
+  if (t.stride_token >= kMaxTokens) return APBV_ERR_UNSUPPORTED;       // the kernels keep row offsets of a 64-row tile in 32 bits
   if (heads > 1 && (t.stride_head < d || t.stride_head % 8)) return APBV_ERR_SHAPE;
   if (batch > 1 && (t.stride_batch <= 0 || t.stride_batch % 8)) return APBV_ERR_SHAPE;
   return APBV_OK;

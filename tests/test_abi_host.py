@@ -71,6 +71,7 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert call_attention(k=ApbvTensor(0x1000, 64, 252, 128, 0)) == -2      # stride not a multiple of 8
     assert call_attention(k=ApbvTensor(0x1000, 64, 64, 128, 0)) == -2       # rows overlap
     assert call_attention(L=0) == -2
+    assert call_attention(k=ApbvTensor(0x1000, 64, 1 << 24, 128, 0)) == -3     # token stride too large for 32-bit tile offsets
 
 
 def call_compress(batch=1, hq=4, hkv=2, d=128, n_q=4, L=64, l_p=8, idx=0x3000, kc=0x4000, vc=0x5000, ws=0x10000,
