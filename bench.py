@@ -33,7 +33,7 @@ PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E, published
 # HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
 # each scaled by the same counter's reading for a copy kernel of known size; see profiles/.  None until
 # measured.
-MEASURED_TRAFFIC_BYTES = (203847 * 2 + 65536) * 1024   # profiles/host_attention_3b-128k_pmc.txt
+MEASURED_TRAFFIC_BYTES = 446905394   # profiles/host_attention_3b-128k_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB)
 
 
 def parse_args():
