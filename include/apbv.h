@@ -2,7 +2,8 @@
  * apbv.h -- C ABI of the MI355X (gfx950) library for one virtual host's share of APB-V's approximate
  * prefill attention (arXiv 2601.21444).
  *
- * Two operations make up the per-layer hot path of a host (Alg. 1):
+ * Two operations make up the per-layer hot path of a host (Alg. 1); a third, apbv_merge_lse, combines the
+ * partial query-block attention results of the hosts (Eq. 5):
  *   apbv_compress_kv     Sec. 3.3 / Alg. 1 "Identify Essential KVs" + "Send Block's Essential KVs":
  *                        score every local key against the query block, keep the l_p best per KV head,
  *                        gather them into the compressed block (K_c, V_c).
@@ -101,7 +102,9 @@ apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_
  *   q_local              Q^(h) [L, Hq, d]
  *   k_anchor, v_anchor   [l_a,   Hkv, d]   l_a  >= 0
  *   k_pass,   v_pass     [n_p,   Hkv, d]   n_p = P*l_p >= 0, blocks of the preceding hosts in host order
- *   k_local,  v_local    [L,     Hkv, d]   L >= 1; row i of q_local is the query of local key i
+ *   k_local,  v_local    [L,     Hkv, d]   row i of q_local is the query of local key i; L == q_local.tokens,
+ *                                          or 0 tokens: no causal segment, every anchor/passing key is visible to
+ *                                          every query (a partial result to be merged by apbv_merge_lse, Eq. 5)
  *   softmax_scale        the paper's 1/sqrt(head_dim); any finite positive value is accepted
  *   out                  [batch, L, Hq, d] bf16, dense
  *   lse_out              optional (may be NULL): [batch, Hq, L] float32, natural-log sum of the
@@ -109,7 +112,8 @@ apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_
  *
  * Arithmetic: bf16 operands, fp32 accumulation and softmax, probabilities rounded to bf16 before the
  * PV product, output rounded to bf16.
- * Supported: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0; each K/V pair must agree in tokens.
+ * Supported: head_dim in {64, 128}; n_q_heads % n_kv_heads == 0; each K/V pair must agree in tokens; at least
+ * one key in total.
  */
 apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim,
                                 apbv_tensor q_local,
@@ -117,6 +121,23 @@ apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int he
                                 apbv_tensor k_pass, apbv_tensor v_pass,
                                 apbv_tensor k_local, apbv_tensor v_local,
                                 float softmax_scale, void* out, float* lse_out, void* hip_stream);
+
+/*
+ * Merge of partial attention results by their log-sum-exp (Eq. 5: A_qr = Merge({A_qr^(h), lse^(h)}_h), "online
+ * softmax" of Sec. 4.2 / App. B.1).  Part h is attention of the SAME queries over its own key set, as produced by
+ * apbv_host_attention with lse_out; over the union of disjoint key sets the exact result is
+ *   A = sum_h w_h A_h / sum_h w_h,  w_h = exp(lse_h - max_h lse_h),  lse = max_h lse_h + log(sum_h w_h).
+ *
+ *   parts_out   n_parts partial outputs, part h at parts_out + h*part_stride_out elements, each [rows, Hq, d] bf16 dense
+ *   parts_lse   n_parts log-sum-exps,    part h at parts_lse + h*part_stride_lse elements, each [Hq, rows] fp32
+ *               (-inf marks a part with no visible key for that row: it contributes nothing)
+ *   out         [rows, Hq, d] bf16;  lse_out optional (may be NULL) [Hq, rows] fp32
+ * 1 <= n_parts <= 65536; head_dim in {64, 128}; parts_out and out 16-byte aligned, strides multiples of 8 / 1.
+ */
+apbv_status apbv_merge_lse(int n_parts, int64_t rows, int n_q_heads, int head_dim,
+                           const void* parts_out, int64_t part_stride_out,
+                           const float* parts_lse, int64_t part_stride_lse,
+                           void* out, float* lse_out, void* hip_stream);
 
 #ifdef __cplusplus
 }

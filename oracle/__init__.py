@@ -12,4 +12,5 @@ from .apbv_oracle import (  # noqa: F401
     make_passing_block,
     visibility_mask,
     host_attention,
+    merge_lse,
 )

@@ -13,6 +13,8 @@ What the paper fixes, and what each function follows:
   the preceding hosts) and Sec. 4.3 (host h sees h*l_p passing keys).
 * ``visibility_mask`` / ``host_attention`` -- Eq. 1 (softmax attention with a mask) applied to the
   concatenated KV of Eq. 4, A_h = Attn(Q^(h), [K_a, K_p^(h), K^(h)], [V_a, V_p^(h), V^(h)]).
+* ``merge_lse`` -- Eq. 5, A_qr = Merge({A_qr^(h), lse^(h)}): partial attention results of the same queries over
+  disjoint key sets are combined with weights exp(lse^(h)) (the "online softmax" of App. B.1).
 
 Readings taken where the paper is silent (all of them are definitions this build adopts):
 
@@ -143,7 +145,8 @@ def host_attention(q: np.ndarray,
                    scale: float,
                    rows: Optional[np.ndarray] = None,
                    chunk: int = 512) -> Tuple[np.ndarray, np.ndarray]:
-    """A_h of Eq. 4 by the definition of Eq. 1, in float64.
+    """A_h of Eq. 4 by the definition of Eq. 1, in float64.  With an empty local segment (``k`` of 0 tokens) every
+    anchor/passing key is visible to every query: a partial result in the sense of Eq. 5.
 
     ``rows`` (optional) restricts the computation to those local query positions; every computed row
     is still a full softmax over its complete masked key set.  ``chunk`` only bounds how many query
@@ -155,7 +158,8 @@ def host_attention(q: np.ndarray,
     v_cat = np.concatenate([bf16_bits_to_f64(v_anchor), bf16_bits_to_f64(v_pass), bf16_bits_to_f64(v)], axis=0)
     l_a, n_pass = k_anchor.shape[0], k_pass.shape[0]
     hkv = k_cat.shape[1]
-    if k.shape[0] != L or hq % hkv or v_cat.shape != k_cat.shape:
+    l_k = k.shape[0]                  # local (causal) keys: L of them, or none (every key visible)
+    if l_k not in (0, L) or hq % hkv or v_cat.shape != k_cat.shape or k_cat.shape[0] == 0:
         raise ValueError("inconsistent shapes")
     g = hq // hkv
     if rows is None:
@@ -166,7 +170,7 @@ def host_attention(q: np.ndarray,
     lse = np.empty((hq, rows.shape[0]), dtype=np.float64)
     for lo in range(0, rows.shape[0], chunk):
         r = rows[lo: lo + chunk]
-        mask = visibility_mask(r, l_a, n_pass, L)              # [r, S_kv]
+        mask = visibility_mask(r, l_a, n_pass, l_k)            # [r, S_kv]
         for h in range(hq):
             kv = h // g
             z = scale * (qq[r, h, :] @ k_cat[:, kv, :].T)      # [r, S_kv]
@@ -176,4 +180,27 @@ def host_attention(q: np.ndarray,
             den = e.sum(axis=1, keepdims=True)
             out[lo: lo + r.shape[0], h, :] = (e @ v_cat[:, kv, :]) / den
             lse[h, lo: lo + r.shape[0]] = (m + np.log(den))[:, 0]
+    return out, lse
+
+
+# --------------------------------------------------------------------------- merge (Eq. 5)
+
+def merge_lse(parts_out: Sequence[np.ndarray], parts_lse: Sequence[np.ndarray]) -> Tuple[np.ndarray, np.ndarray]:
+    """Combine partial attention results over disjoint key sets (Eq. 5).
+
+    ``parts_out[h]`` is ``[rows, Hq, d]`` (float64), ``parts_lse[h]`` is ``[Hq, rows]`` with the natural-log sum of
+    exponentials of part h's scaled logits (``-inf`` for a part that saw no key).  Returns ``(A, lse)`` with
+    ``A = sum_h e^{lse_h} A_h / sum_h e^{lse_h}`` and ``lse = log sum_h e^{lse_h}``, evaluated with the maximum
+    factored out."""
+    outs = np.stack([np.asarray(a, dtype=np.float64) for a in parts_out])        # [n, rows, Hq, d]
+    lses = np.stack([np.asarray(a, dtype=np.float64) for a in parts_lse])        # [n, Hq, rows]
+    m = lses.max(axis=0)                                                          # [Hq, rows]
+    m_safe = np.where(np.isfinite(m), m, 0.0)
+    w = np.exp(lses - m_safe[None])                                               # exp(-inf) = 0
+    den = w.sum(axis=0)                                                           # [Hq, rows]
+    w_rhd = np.transpose(w, (0, 2, 1))[..., None]                                 # [n, rows, Hq, 1]
+    with np.errstate(invalid="ignore", divide="ignore"):
+        out = (w_rhd * outs).sum(axis=0) / np.transpose(den)[..., None]
+        lse = m_safe + np.log(den)
+    out = np.where(np.transpose(den)[..., None] > 0, out, 0.0)
     return out, lse

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     apbv_compress_kv,
     apbv_compress_workspace_bytes,
     apbv_host_attention,
+    apbv_merge_lse,
     apbv_version,
     load_library,
     status_string,

@@ -60,6 +60,11 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
         ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor,
         ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.apbv_merge_lse.restype = ctypes.c_int
+    lib.apbv_merge_lse.argtypes = [
+        ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+        ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
+        ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -158,7 +163,7 @@ def apbv_host_attention(q_local: torch.Tensor, k_anchor: torch.Tensor, v_anchor:
             raise ValueError("batch sizes differ")
         views.append(view)
     L, hq, d = q_local.shape[-3], q_local.shape[-2], q_local.shape[-1]
-    hkv = k_local.shape[-2]
+    hkv = k_anchor.shape[-2]
     dev = q_local.device
     if out is None:
         out = torch.empty((b, L, hq, d), dtype=torch.bfloat16, device=dev)
@@ -171,4 +176,30 @@ def apbv_host_attention(q_local: torch.Tensor, k_anchor: torch.Tensor, v_anchor:
     if not batched:
         out = out[0] if out.dim() == 4 else out
         lse_out = lse_out[0] if (lse_out is not None and lse_out.dim() == 3) else lse_out
+    return (out, lse_out) if return_lse else out
+
+
+def apbv_merge_lse(parts_out: torch.Tensor, parts_lse: torch.Tensor, *, return_lse: bool = False,
+                   out: Optional[torch.Tensor] = None, lse_out: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None):
+    """Merge partial attention results; see apbv_merge_lse in include/apbv.h.
+    ``parts_out [n_parts, rows, Hq, d]`` bf16 (parts may be strided along dim 0), ``parts_lse [n_parts, Hq, rows]``
+    fp32.  Returns ``out [rows, Hq, d]`` bf16 (and ``lse [Hq, rows]`` fp32)."""
+    lib = load_library()
+    if parts_out.dtype != torch.bfloat16 or parts_lse.dtype != torch.float32:
+        raise TypeError("expected bfloat16 partial outputs and float32 log-sum-exps")
+    n, rows, hq, d = parts_out.shape
+    if parts_lse.shape != (n, hq, rows):
+        raise ValueError("parts_lse must be [n_parts, Hq, rows]")
+    if not parts_out[0].is_contiguous() or not parts_lse[0].is_contiguous():
+        raise ValueError("each part must be dense")
+    if out is None:
+        out = torch.empty((rows, hq, d), dtype=torch.bfloat16, device=parts_out.device)
+    if return_lse and lse_out is None:
+        lse_out = torch.empty((hq, rows), dtype=torch.float32, device=parts_out.device)
+    st = lib.apbv_merge_lse(n, rows, hq, d, parts_out.data_ptr(), parts_out.stride(0), parts_lse.data_ptr(),
+                            parts_lse.stride(0), out.data_ptr(), lse_out.data_ptr() if lse_out is not None else None,
+                            _stream_ptr(stream))
+    if st != 0:
+        raise ApbvError(st, "apbv_merge_lse")
     return (out, lse_out) if return_lse else out

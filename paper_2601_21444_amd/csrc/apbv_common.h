@@ -41,15 +41,28 @@ struct AttnParams {
   View v_seg[3];
   bf16_t* out;            // [batch, L, Hq, d]
   float* lse;             // [batch, Hq, L] or nullptr
-  int64_t L;              // local block length
+  int64_t L;              // query rows (= local block length when there is a local segment)
   int64_t l_a;            // anchor length
   int64_t n_vis;          // l_a + n_p: keys visible to every query
-  int64_t s_kv;           // n_vis + L
+  int64_t s_kv;           // n_vis + local keys (L of them, or none)
   int batch, hq, hkv, group;
   float scale_log2;       // softmax_scale * log2(e)
 };
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream);
+
+// ---- merge of partial attention results -------------------------------------------------------
+struct MergeParams {
+  const bf16_t* parts_out;   // [n_parts][rows, Hq, d]
+  const float* parts_lse;    // [n_parts][Hq, rows]
+  int64_t stride_out;        // elements between parts
+  int64_t stride_lse;
+  bf16_t* out;               // [rows, Hq, d]
+  float* lse_out;            // optional [Hq, rows]
+  int64_t rows;
+  int n_parts, hq, d;
+};
+apbv_status launch_merge_lse(const MergeParams& p, hipStream_t stream);
 
 // ---- compression ------------------------------------------------------------------------------
 struct CompressParams {

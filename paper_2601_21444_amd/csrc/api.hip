@@ -103,14 +103,15 @@ apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int he
   apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
   if (st != APBV_OK) return st;
   if ((st = check_view(q_local, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
+  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
   if ((st = check_view(k_anchor, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
   if ((st = check_view(v_anchor, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
   if ((st = check_view(k_pass, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
   if ((st = check_view(v_pass, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if (q_local.tokens != k_local.tokens || v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
+  if ((k_local.tokens != 0 && q_local.tokens != k_local.tokens) || v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
   if (v_anchor.tokens != k_anchor.tokens || v_pass.tokens != k_pass.tokens) return APBV_ERR_SHAPE;
+  if (k_anchor.tokens + k_pass.tokens + k_local.tokens < 1) return APBV_ERR_SHAPE;       // every query needs a key
   if (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale)) return APBV_ERR_SHAPE;
   if (out == nullptr) return APBV_ERR_NULL;
   if (!aligned(out, 16) || (lse_out != nullptr && !aligned(lse_out, 4))) return APBV_ERR_SHAPE;
@@ -125,16 +126,43 @@ apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int he
   p.v_seg[2] = to_view(v_local);
   p.out = static_cast<bf16_t*>(out);
   p.lse = lse_out;
-  p.L = k_local.tokens;
+  p.L = q_local.tokens;
   p.l_a = k_anchor.tokens;
   p.n_vis = k_anchor.tokens + k_pass.tokens;
-  p.s_kv = p.n_vis + p.L;
+  p.s_kv = p.n_vis + k_local.tokens;
   p.batch = batch;
   p.hq = n_q_heads;
   p.hkv = n_kv_heads;
   p.group = n_q_heads / n_kv_heads;
   p.scale_log2 = softmax_scale * 1.4426950408889634f;
   return launch_host_attention(p, head_dim, static_cast<hipStream_t>(hip_stream));
+}
+
+apbv_status apbv_merge_lse(int n_parts, int64_t rows, int n_q_heads, int head_dim, const void* parts_out,
+                           int64_t part_stride_out, const float* parts_lse, int64_t part_stride_lse, void* out,
+                           float* lse_out, void* hip_stream) {
+  if (n_parts < 1 || n_parts > 65536 || rows < 1 || rows > kMaxTokens || n_q_heads < 1 || n_q_heads > 65535)
+    return APBV_ERR_SHAPE;
+  if (head_dim != 64 && head_dim != 128) return APBV_ERR_UNSUPPORTED;
+  if (parts_out == nullptr || parts_lse == nullptr || out == nullptr) return APBV_ERR_NULL;
+  if (!aligned(parts_out, 16) || !aligned(out, 16) || !aligned(parts_lse, 4) || (lse_out != nullptr && !aligned(lse_out, 4)))
+    return APBV_ERR_SHAPE;
+  if (n_parts > 1) {
+    if (part_stride_out < rows * n_q_heads * head_dim || part_stride_out % 8) return APBV_ERR_SHAPE;
+    if (part_stride_lse < rows * n_q_heads) return APBV_ERR_SHAPE;
+  }
+  MergeParams p;
+  p.parts_out = static_cast<const bf16_t*>(parts_out);
+  p.parts_lse = parts_lse;
+  p.stride_out = part_stride_out;
+  p.stride_lse = part_stride_lse;
+  p.out = static_cast<bf16_t*>(out);
+  p.lse_out = lse_out;
+  p.rows = rows;
+  p.n_parts = n_parts;
+  p.hq = n_q_heads;
+  p.d = head_dim;
+  return launch_merge_lse(p, static_cast<hipStream_t>(hip_stream));
 }
 
 }  // extern "C"

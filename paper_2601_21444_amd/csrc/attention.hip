@@ -4,7 +4,8 @@
 // Mask.  The three KV segments are walked as ONE virtual key axis j in [0, n_vis + L): anchor and
 // passing keys (j < n_vis) are visible to every query and local key j - n_vis is visible to query i iff
 // j - n_vis <= i, so the whole mask is the single test  j <= i + n_vis  (a causal mask shifted by
-// n_vis).  Key tiles that lie entirely above that diagonal are never visited, and only tiles that
+// n_vis).  Without a local segment (partial attention of a query block over context keys only, merged
+// later by log-sum-exp) the bound is simply the last key.  Key tiles that lie entirely above that diagonal are never visited, and only tiles that
 // touch it pay for the comparison.
 //
 // Tiling.  A workgroup of 8 waves (two per SIMD, one workgroup per CU) owns 256 consecutive query
@@ -259,11 +260,14 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   float l_run = 0.f;         // running sum of the bf16-rounded exp2(. - m_ref), this lane half only
 
   // Keys the workgroup / this wave can see at all.
+  // Query i sees the virtual keys 0 .. min(i + n_vis, s_kv - 1); the second bound only matters when there is no
+  // causal segment (s_kv == n_vis: every key visible to every query).
+  auto last_key = [&](int64_t i) { return (i + p.n_vis < p.s_kv - 1) ? i + p.n_vis : p.s_kv - 1; };
   const int64_t i_last_wg = (i0 + kBM - 1 < p.L - 1) ? i0 + kBM - 1 : p.L - 1;
-  const int n_tiles = (int)((i_last_wg + 1 + p.n_vis + kBN - 1) / kBN);
-  const int t_last_wave = (int)((iw + 31 + p.n_vis) / kBN);   // last tile any row of the wave can see into
-  const int t_mask_wave = (int)((iw + p.n_vis + 1) / kBN);    // first tile that reaches above the wave's diagonal
-  const int jrel0 = (int)(i_row + p.n_vis);                   // last visible virtual key of this lane's query
+  const int n_tiles = (int)(last_key(i_last_wg) / kBN) + 1;
+  const int t_last_wave = (int)(last_key(iw + 31) / kBN);     // last tile any row of the wave can see into
+  const int t_mask_wave = (int)((last_key(iw) + 1) / kBN);    // first tile with a key some row of the wave cannot see
+  const int jrel0 = (int)last_key(i_row);                     // last visible virtual key of this lane's query
 
   auto compute = [&](const unsigned char* kt, const unsigned char* vt, int t) {
     if (t > t_last_wave) return;

@@ -1,0 +1,68 @@
+// Merge of partial attention results by their log-sum-exp (Eq. 5: A_qr = Merge({A_qr^(h), lse^(h)})).
+//
+// Each part h is softmax attention of the same queries over its own set of keys, with
+// lse_h = log sum exp of its scaled logits.  Over the union of disjoint key sets the exact result is
+//   A = sum_h w_h A_h / sum_h w_h,   w_h = exp(lse_h - max_h lse_h),   lse = max_h lse_h + log sum_h w_h.
+// Memory-bound: every partial output is read once (16 bytes per thread per part), fp32 arithmetic.
+#include "apbv_common.h"
+
+namespace apbv {
+namespace {
+
+template <int D>
+__global__ __launch_bounds__(256) void merge_lse_kernel(const MergeParams p) {
+  constexpr int KC = D / 8;
+  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;       // over rows * hq * KC
+  if (item >= p.rows * p.hq * KC) return;
+  const int c = (int)(item % KC);
+  const int64_t rh = item / KC;                                         // row * hq + head
+  const int h = (int)(rh % p.hq);
+  const int64_t row = rh / p.hq;
+  const int64_t lse_idx = (int64_t)h * p.rows + row;
+
+  float m = -INFINITY;
+  for (int s = 0; s < p.n_parts; ++s) m = fmaxf(m, p.parts_lse[s * p.stride_lse + lse_idx]);
+  float acc[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+  float wsum = 0.f;
+  if (m > -INFINITY) {
+    for (int s = 0; s < p.n_parts; ++s) {
+      const float w = __expf(p.parts_lse[s * p.stride_lse + lse_idx] - m);     // exp(-inf) = 0: empty parts drop out
+      const u32x4 x = *reinterpret_cast<const u32x4*>(p.parts_out + s * p.stride_out + rh * D + 8 * c);
+      wsum += w;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] = __builtin_fmaf(w, __uint_as_float(x[e] << 16), acc[2 * e]);
+        acc[2 * e + 1] = __builtin_fmaf(w, __uint_as_float(x[e] & 0xffff0000u), acc[2 * e + 1]);
+      }
+    }
+  }
+  const float inv = wsum > 0.f ? 1.0f / wsum : 0.f;
+  u32x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    f32x2 xy = {acc[2 * e] * inv, acc[2 * e + 1] * inv};
+    bf16x2 b = __builtin_convertvector(xy, bf16x2);
+    o[e] = __builtin_bit_cast(uint32_t, b);
+  }
+  *reinterpret_cast<u32x4*>(p.out + rh * D + 8 * c) = o;
+  if (p.lse_out != nullptr && c == 0) p.lse_out[lse_idx] = wsum > 0.f ? m + __logf(wsum) : -INFINITY;
+}
+
+}  // namespace
+
+apbv_status launch_merge_lse(const MergeParams& p, hipStream_t stream) {
+  const int64_t items = p.rows * p.hq * (p.d / 8);
+  const int64_t blocks = (items + 255) / 256;
+  if (blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
+  if (p.d == 128)
+    hipLaunchKernelGGL(merge_lse_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else if (p.d == 64)
+    hipLaunchKernelGGL(merge_lse_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream, p);
+  else
+    return APBV_ERR_UNSUPPORTED;
+  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+}
+
+}  // namespace apbv

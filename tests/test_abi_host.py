@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = apbv.load_library()
     names = declared_symbols()
-    assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention",
+    assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_merge_lse",
                      "apbv_status_string", "apbv_version"]
     for n in names:
         assert getattr(lib, n) is not None
@@ -71,6 +71,8 @@ def test_attention_rejects_bad_arguments_without_launching():
     assert call_attention(k=ApbvTensor(0x1000, 64, 252, 128, 0)) == -2      # stride not a multiple of 8
     assert call_attention(k=ApbvTensor(0x1000, 64, 64, 128, 0)) == -2       # rows overlap
     assert call_attention(L=0) == -2
+    assert call_attention(k=view(0, 2, 128), v=view(0, 2, 128), l_a=0, n_p=0) == -2       # no key at all
+    assert call_attention(k=view(0, 2, 128)) == -2                                        # K/V local mismatch
     assert call_attention(k=ApbvTensor(0x1000, 64, 1 << 24, 128, 0)) == -3     # token stride too large for 32-bit tile offsets
 
 
@@ -90,6 +92,16 @@ def test_compress_rejects_bad_arguments_without_launching():
     assert call_compress(n_q=0) == -2
     assert call_compress(v=view(63, 2, 128)) == -2
     assert call_compress(kc=0x4002) == -2
+
+
+def test_merge_rejects_bad_arguments_without_launching():
+    lib = apbv.load_library()
+
+    def call(n=2, rows=8, hq=4, d=128, po=0x1000, so=8 * 4 * 128, pl=0x9000, sl=32, out=0x20000):
+        return lib.apbv_merge_lse(n, rows, hq, d, po, so, pl, sl, out, None, None)
+    assert call(n=0) == -2 and call(rows=0) == -2 and call(d=96) == -3
+    assert call(po=None) == -1 and call(pl=None) == -1 and call(out=None) == -1
+    assert call(po=0x1008) == -2 and call(so=100) == -2 and call(sl=31) == -2
 
 
 def test_product_path_has_no_oracle_or_cpu_fallback():

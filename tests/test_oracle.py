@@ -254,6 +254,47 @@ def test_visibility_mask_counts_match_closed_forms():
     assert ours == paper - 2 * l_a * l_a * d + 8 * l_a * L * d + 4 * L * d
 
 
+# ------------------------------------------------------------------ merge pins (Eq. 5)
+
+def test_merge_handworked():
+    """Two parts with sum-of-exponentials 2 and 6: weights 1/4 and 3/4; a third part that saw no key drops out."""
+    a0 = np.array([[[4.0, 0.0]]])            # [rows=1, Hq=1, d=2]
+    a1 = np.array([[[0.0, 8.0]]])
+    a2 = np.array([[[100.0, 100.0]]])
+    out, lse = oracle.merge_lse([a0, a1, a2], [np.array([[math.log(2)]]), np.array([[math.log(6)]]), np.array([[-np.inf]])])
+    np.testing.assert_allclose(out[0, 0], [1.0, 6.0], atol=1e-14)
+    assert lse[0, 0] == pytest.approx(math.log(8), abs=1e-14)
+    out, lse = oracle.merge_lse([a2], [np.array([[-np.inf]])])      # nothing visible at all
+    assert np.all(out == 0) and lse[0, 0] == -np.inf
+
+
+def test_merge_of_partition_equals_attention_over_the_union():
+    """Attention over [anchor | context | own causal block] equals the merge of three partial attentions over
+    those three key sets (the identity Eq. 5 relies on); a non-disjoint split must NOT reproduce it."""
+    rng = np.random.default_rng(17)
+    hq, hkv, d, l_a, n_c, L = 4, 2, 8, 9, 21, 13
+    q = rand_bits(rng, (L, hq, d))
+    ka, va, kc, vc, k, v = (rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_c, n_c, L, L))
+    e = np.empty((0, hkv, d), dtype=np.uint16)
+    full, lse_full = oracle.host_attention(q, ka, va, kc, vc, k, v, 0.4)
+    p0 = oracle.host_attention(q, ka, va, e, e, e, e, 0.4)            # anchor only, all visible
+    p1 = oracle.host_attention(q, e, e, kc, vc, e, e, 0.4)            # context only, all visible
+    p2 = oracle.host_attention(q, e, e, e, e, k, v, 0.4)              # own block, causal
+    out, lse = oracle.merge_lse([p0[0], p1[0], p2[0]], [p0[1], p1[1], p2[1]])
+    np.testing.assert_allclose(out, full, atol=1e-12)
+    np.testing.assert_allclose(lse, lse_full, atol=1e-12)
+    # merging is order independent
+    out2, _ = oracle.merge_lse([p2[0], p0[0], p1[0]], [p2[1], p0[1], p1[1]])
+    np.testing.assert_allclose(out2, out, atol=1e-13)
+    # counting the anchor twice changes the result
+    out3, _ = oracle.merge_lse([p0[0], p0[0], p1[0], p2[0]], [p0[1], p0[1], p1[1], p2[1]])
+    assert np.abs(out3 - full).max() > 1e-3
+    # a partial with no causal segment sees every key from every row
+    qf, kf, vf = (oracle.bf16_bits_to_f64(x) for x in (q, kc, vc))
+    z = 0.4 * qf[:, 0] @ kf[:, 0].T
+    np.testing.assert_allclose(p1[0][:, 0], scipy.special.softmax(z, axis=1) @ vf[:, 0], atol=1e-13)
+
+
 # ------------------------------------------------------------------ scoring pins
 
 def frac(bits_arr):
