@@ -2,8 +2,8 @@
  * apbv.h -- C ABI of the MI355X (gfx950) library for one virtual host's share of APB-V's approximate
  * prefill attention (arXiv 2601.21444).
  *
- * Two operations make up the per-layer hot path of a host (Alg. 1); a third, apbv_merge_lse, combines the
- * partial query-block attention results of the hosts (Eq. 5):
+ * Two operations make up the per-layer hot path of a host (Alg. 1); apbv_query_attention and apbv_merge_lse
+ * serve the query block: its partial attention on every host and the merge of those results (Eq. 5):
  *   apbv_compress_kv     Sec. 3.3 / Alg. 1 "Identify Essential KVs" + "Send Block's Essential KVs":
  *                        score every local key against the query block, keep the l_p best per KV head,
  *                        gather them into the compressed block (K_c, V_c).
@@ -138,6 +138,32 @@ apbv_status apbv_merge_lse(int n_parts, int64_t rows, int n_q_heads, int head_di
                            const void* parts_out, int64_t part_stride_out,
                            const float* parts_lse, int64_t part_stride_lse,
                            void* out, float* lse_out, void* hip_stream);
+
+/* Host, pure.  Bytes of workspace apbv_query_attention needs (256-byte aligned; 0 when the call would not split
+ * the keys, and 0 on invalid arguments).  n_keys = l_a + n_p + local keys; n_splits as passed to the call. */
+size_t apbv_query_attention_workspace_bytes(int batch, int n_q_heads, int head_dim, int64_t n_q, int64_t n_keys,
+                                            int n_splits);
+
+/*
+ * Attention of a SHORT query block over a host's keys (Eq. 5: A_qr^(h), lse^(h) = Attn(Q_qr, K, V); also the
+ * decoding-time attention of Sec. 4.2).  Same operation, arguments, layouts and arithmetic as apbv_host_attention;
+ * the difference is the launch: a block of a few hundred queries yields too few (query tile x head) work items to
+ * fill the GPU, so the key axis is cut into ranges that run in parallel, each producing a normalised partial result
+ * and its log-sum-exp in the workspace, combined by the merge of apbv_merge_lse in a second kernel.  Partial
+ * results pass through bf16, so the output can differ from apbv_host_attention's by bf16 rounding of the parts.
+ *
+ *   n_splits   0: chosen by the library from the shape; >= 1: requested number of key ranges (clipped to the number
+ *              of 64-key tiles and to 256; 1 = no split, the call is then apbv_host_attention and needs no workspace)
+ *   workspace / workspace_bytes   at least apbv_query_attention_workspace_bytes(...) bytes, 256-byte aligned; may be
+ *              NULL / 0 when that is 0.  Contents need no initialisation and are garbage afterwards.
+ */
+apbv_status apbv_query_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                                 apbv_tensor q_block,
+                                 apbv_tensor k_anchor, apbv_tensor v_anchor,
+                                 apbv_tensor k_pass, apbv_tensor v_pass,
+                                 apbv_tensor k_local, apbv_tensor v_local,
+                                 float softmax_scale, int n_splits, void* out, float* lse_out,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     apbv_compress_workspace_bytes,
     apbv_host_attention,
     apbv_merge_lse,
+    apbv_query_attention,
+    apbv_query_attention_workspace_bytes,
     apbv_version,
     load_library,
     status_string,

@@ -65,6 +65,15 @@ def load_library() -> ctypes.CDLL:
         ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
         ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64,
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+    lib.apbv_query_attention_workspace_bytes.restype = ctypes.c_size_t
+    lib.apbv_query_attention_workspace_bytes.argtypes = [
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int]
+    lib.apbv_query_attention.restype = ctypes.c_int
+    lib.apbv_query_attention.argtypes = [
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor,
+        ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+        ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -173,6 +182,52 @@ def apbv_host_attention(q_local: torch.Tensor, k_anchor: torch.Tensor, v_anchor:
                                  lse_out.data_ptr() if lse_out is not None else None, _stream_ptr(stream))
     if st != 0:
         raise ApbvError(st, "apbv_host_attention")
+    if not batched:
+        out = out[0] if out.dim() == 4 else out
+        lse_out = lse_out[0] if (lse_out is not None and lse_out.dim() == 3) else lse_out
+    return (out, lse_out) if return_lse else out
+
+
+def apbv_query_attention_workspace_bytes(batch: int, n_q_heads: int, head_dim: int, n_q: int, n_keys: int,
+                                         n_splits: int = 0) -> int:
+    return int(load_library().apbv_query_attention_workspace_bytes(batch, n_q_heads, head_dim, n_q, n_keys, n_splits))
+
+
+def apbv_query_attention(q_block: torch.Tensor, k_anchor: torch.Tensor, v_anchor: torch.Tensor,
+                         k_pass: torch.Tensor, v_pass: torch.Tensor, k_local: torch.Tensor, v_local: torch.Tensor,
+                         softmax_scale: float, *, n_splits: int = 0, return_lse: bool = False,
+                         out: Optional[torch.Tensor] = None, lse_out: Optional[torch.Tensor] = None,
+                         workspace: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """Attention of a short query block with the key axis split over workgroups; see apbv_query_attention in
+    include/apbv.h.  Same tensors and results as :func:`apbv_host_attention`."""
+    lib = load_library()
+    batched = q_block.dim() == 4
+    views = []
+    b = None
+    for t in (q_block, k_anchor, v_anchor, k_pass, v_pass, k_local, v_local):
+        view, bt = tensor_view(t)
+        if b is None:
+            b = bt
+        elif bt != b:
+            raise ValueError("batch sizes differ")
+        views.append(view)
+    n_q, hq, d = q_block.shape[-3], q_block.shape[-2], q_block.shape[-1]
+    hkv = k_anchor.shape[-2]
+    n_keys = k_anchor.shape[-3] + k_pass.shape[-3] + k_local.shape[-3]
+    dev = q_block.device
+    if out is None:
+        out = torch.empty((b, n_q, hq, d), dtype=torch.bfloat16, device=dev)
+    if return_lse and lse_out is None:
+        lse_out = torch.empty((b, hq, n_q), dtype=torch.float32, device=dev)
+    if workspace is None:
+        nbytes = apbv_query_attention_workspace_bytes(b, hq, d, n_q, max(n_keys, 1), n_splits)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    st = lib.apbv_query_attention(b, hq, hkv, d, *views, float(softmax_scale), int(n_splits), out.data_ptr(),
+                                  lse_out.data_ptr() if lse_out is not None else None,
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                  _stream_ptr(stream))
+    if st != 0:
+        raise ApbvError(st, "apbv_query_attention")
     if not batched:
         out = out[0] if out.dim() == 4 else out
         lse_out = lse_out[0] if (lse_out is not None and lse_out.dim() == 3) else lse_out

@@ -47,20 +47,26 @@ struct AttnParams {
   int64_t s_kv;           // n_vis + local keys (L of them, or none)
   int batch, hq, hkv, group;
   float scale_log2;       // softmax_scale * log2(e)
+  // key split: n_splits ranges of tiles_per_split 64-key tiles; split s writes its partial result at
+  // out + s*split_stride_out and lse + s*split_stride_lse (n_splits == 1: the plain call)
+  int n_splits, tiles_per_split;
+  int64_t split_stride_out, split_stride_lse;
 };
+constexpr int kAttnKeyTile = 64;      // keys per tile of the attention kernel
+constexpr int kAttnQueryTile = 256;   // query rows per workgroup
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream);
 
 // ---- merge of partial attention results -------------------------------------------------------
 struct MergeParams {
-  const bf16_t* parts_out;   // [n_parts][rows, Hq, d]
-  const float* parts_lse;    // [n_parts][Hq, rows]
+  const bf16_t* parts_out;   // [n_parts][batch, rows, Hq, d]
+  const float* parts_lse;    // [n_parts][batch, Hq, rows]
   int64_t stride_out;        // elements between parts
   int64_t stride_lse;
-  bf16_t* out;               // [rows, Hq, d]
-  float* lse_out;            // optional [Hq, rows]
+  bf16_t* out;               // [batch, rows, Hq, d]
+  float* lse_out;            // optional [batch, Hq, rows]
   int64_t rows;
-  int n_parts, hq, d;
+  int n_parts, hq, d, batch;
 };
 apbv_status launch_merge_lse(const MergeParams& p, hipStream_t stream);
 

@@ -33,6 +33,10 @@
 // rescaled) when it would grow by more than 2^8, which keeps exp2 arguments <= 8 and removes the
 // per-tile rescale of the 64 accumulator registers from the common path.
 //
+// Key split.  For a short query block (few query tiles) the key axis can be cut into n_splits ranges of
+// tiles_per_split tiles, one workgroup each; every range writes a normalised partial result and
+// its log-sum-exp, merged afterwards (Eq. 5's merge).  n_splits = 1 is the plain kernel.
+//
 // Launch.  One workgroup per (query tile, query head, batch item), heaviest query tiles first.  The
 // linear workgroup id is decoded so that the G query heads that share a KV head run on the same XCD
 // (workgroup id modulo 8) back to back and stream the same K/V tiles through that XCD's L2.
@@ -114,14 +118,14 @@ struct TileStream {
   __device__ __forceinline__ int row(int u) const { return (wave * T::IPW + u) * T::RPI + lane / T::KC; }
   __device__ __forceinline__ uint32_t ldst(int u) const { return (uint32_t)((wave * T::IPW + u) * T::RPI * T::ROW_BYTES); }
 
-  __device__ __forceinline__ void init(const Segs& k, const Segs& v, int64_t skv, int w, int l) {
+  __device__ __forceinline__ void init(const Segs& k, const Segs& v, int64_t skv, int w, int l, int t_first) {
     ks = k;
     vs = v;
     s_kv = skv;
     wave = w;
     lane = l;
-    t_next = 0;
-    run_end = 0;
+    t_next = t_first;
+    run_end = t_first;
     kb = vb = nullptr;
     kstep = vstep = 0;
 #pragma unroll
@@ -190,8 +194,10 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   // ---- workgroup -> (query tile, head, batch); the heads of one KV group share an XCD
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
-  const int item = (slot / p.group) * kXcds + xcd;
-  if (item >= n_items) return;
+  const int item_split = (slot / p.group) * kXcds + xcd;
+  if (item_split >= n_items) return;
+  const int split = item_split % p.n_splits;     // key ranges of one item share nothing: spread them over the XCDs
+  const int item = item_split / p.n_splits;
   const int g = slot % p.group;
   const int bh = p.batch * p.hkv;
   const int qt = n_qtiles - 1 - item / bh;       // heaviest query tiles first
@@ -264,7 +270,10 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   // causal segment (s_kv == n_vis: every key visible to every query).
   auto last_key = [&](int64_t i) { return (i + p.n_vis < p.s_kv - 1) ? i + p.n_vis : p.s_kv - 1; };
   const int64_t i_last_wg = (i0 + kBM - 1 < p.L - 1) ? i0 + kBM - 1 : p.L - 1;
-  const int n_tiles = (int)(last_key(i_last_wg) / kBN) + 1;
+  const int n_tiles_vis = (int)(last_key(i_last_wg) / kBN) + 1;      // tiles the workgroup can see into
+  // key split (partial results merged afterwards): this workgroup walks tiles [t_begin, n_tiles) only
+  const int t_begin = split * p.tiles_per_split;
+  const int n_tiles = (t_begin + p.tiles_per_split < n_tiles_vis) ? t_begin + p.tiles_per_split : n_tiles_vis;
   const int t_last_wave = (int)(last_key(iw + 31) / kBN);     // last tile any row of the wave can see into
   const int t_mask_wave = (int)((last_key(iw) + 1) / kBN);    // first tile with a key some row of the wave cannot see
   const int jrel0 = (int)last_key(i_row);                     // last visible virtual key of this lane's query
@@ -328,7 +337,8 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
     }
     const float m_new = fmaxf(m_ref, mx * p.scale_log2);
     if (__builtin_amdgcn_ballot_w64(m_new > m_ref + kRescaleThreshold) != 0) {
-      const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);    // m_ref = -inf on the first tile: alpha = 0
+      // m_ref = -inf before the first visible key: alpha = 0; a row still without one (m_new = -inf) keeps its zeros
+      const float alpha = m_new > -INFINITY ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.f;
       m_ref = m_new;
       l_run *= alpha;
 #pragma unroll
@@ -336,10 +346,13 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[d][r] *= alpha;
     }
+    // (a row that has not seen a visible key yet -- possible in a key split -- keeps m_ref = -inf: subtract 0,
+    // every probability is exp2(-inf) = 0)
+    const float m_sub = m_ref > -INFINITY ? m_ref : 0.f;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], p.scale_log2, -m_ref));
+      for (int r = 0; r < 16; ++r) s[kb][r] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[kb][r], p.scale_log2, -m_sub));
 
     // ---- O^T += V^T P^T
 #pragma unroll
@@ -370,13 +383,13 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 
   // ---- key loop: LDS double buffer, the loads of tile t+1 in flight while tile t is computed
   TileStream<D> ts;
-  ts.init(ks, vs, p.s_kv, wave, lane);
+  ts.init(ks, vs, p.s_kv, wave, lane, t_begin);
   const uint32_t k0 = lds_addr(k_lds0), k1 = lds_addr(k_lds1), v0 = lds_addr(v_lds0), v1 = lds_addr(v_lds1);
   // The Q fragments are in (vmcnt 0, other counters untouched): from here on only tile loads are
   // outstanding, and the compiler knows it need not wait for vector memory inside the loop.
   __builtin_amdgcn_s_waitcnt(0x0F70);
-  ts.issue(k0, v0);
-  for (int t = 0; t < n_tiles; t += 2) {
+  if (t_begin < n_tiles) ts.issue(k0, v0);
+  for (int t = t_begin; t < n_tiles; t += 2) {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of tile t has landed
     __syncthreads();                                  // ... everyone's has, and everyone is done with the other buffer
     if (t + 1 < n_tiles) ts.issue(k1, v1);
@@ -394,9 +407,9 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
     auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(l_run), __float_as_uint(l_run), false, false);
     l_tot = __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
   }
-  const float inv = 1.0f / l_tot;
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;     // a key split may leave a row without any visible key
   if (i_row < p.L) {
-    bf16_t* orow = p.out + (((int64_t)b * p.L + i_row) * p.hq + h) * D;
+    bf16_t* orow = p.out + (int64_t)split * p.split_stride_out + (((int64_t)b * p.L + i_row) * p.hq + h) * D;
 #pragma unroll
     for (int d = 0; d < T::DB; ++d)
 #pragma unroll
@@ -411,7 +424,8 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
         *reinterpret_cast<u32x2*>(orow + 32 * d + 8 * gq + 4 * hh) = w;
       }
     if (p.lse != nullptr && hh == 0)
-      p.lse[((int64_t)b * p.hq + h) * p.L + i_row] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+      p.lse[(int64_t)split * p.split_stride_lse + ((int64_t)b * p.hq + h) * p.L + i_row] =
+          l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f : -INFINITY;
   }
 }
 
@@ -419,7 +433,7 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream) {
   const int n_qtiles = (int)((p.L + kBM - 1) / kBM);
-  const int64_t n_items = (int64_t)n_qtiles * p.batch * p.hkv;
+  const int64_t n_items = (int64_t)n_qtiles * p.batch * p.hkv * p.n_splits;
   const int64_t n_blocks = (n_items + kXcds - 1) / kXcds * kXcds * p.group;
   if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_blocks);

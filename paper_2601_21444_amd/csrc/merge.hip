@@ -12,13 +12,14 @@ namespace {
 template <int D>
 __global__ __launch_bounds__(256) void merge_lse_kernel(const MergeParams p) {
   constexpr int KC = D / 8;
-  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;       // over rows * hq * KC
-  if (item >= p.rows * p.hq * KC) return;
+  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;       // over batch * rows * hq * KC
+  if (item >= (int64_t)p.batch * p.rows * p.hq * KC) return;
   const int c = (int)(item % KC);
-  const int64_t rh = item / KC;                                         // row * hq + head
+  const int64_t rh = item / KC;                                         // (b * rows + row) * hq + head
   const int h = (int)(rh % p.hq);
-  const int64_t row = rh / p.hq;
-  const int64_t lse_idx = (int64_t)h * p.rows + row;
+  const int64_t brow = rh / p.hq;
+  const int64_t row = brow % p.rows, b = brow / p.rows;
+  const int64_t lse_idx = (b * p.hq + h) * p.rows + row;
 
   float m = -INFINITY;
   for (int s = 0; s < p.n_parts; ++s) m = fmaxf(m, p.parts_lse[s * p.stride_lse + lse_idx]);
@@ -53,7 +54,7 @@ __global__ __launch_bounds__(256) void merge_lse_kernel(const MergeParams p) {
 }  // namespace
 
 apbv_status launch_merge_lse(const MergeParams& p, hipStream_t stream) {
-  const int64_t items = p.rows * p.hq * (p.d / 8);
+  const int64_t items = (int64_t)p.batch * p.rows * p.hq * (p.d / 8);
   const int64_t blocks = (items + 255) / 256;
   if (blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
   if (p.d == 128)

@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     lib = apbv.load_library()
     names = declared_symbols()
     assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_merge_lse",
-                     "apbv_status_string", "apbv_version"]
+                     "apbv_query_attention", "apbv_query_attention_workspace_bytes", "apbv_status_string",
+                     "apbv_version"]
     for n in names:
         assert getattr(lib, n) is not None
     assert apbv.apbv_version() >= 100
@@ -102,6 +103,27 @@ def test_merge_rejects_bad_arguments_without_launching():
     assert call(n=0) == -2 and call(rows=0) == -2 and call(d=96) == -3
     assert call(po=None) == -1 and call(pl=None) == -1 and call(out=None) == -1
     assert call(po=0x1008) == -2 and call(so=100) == -2 and call(sl=31) == -2
+
+
+def test_query_attention_workspace_plan_and_rejections():
+    lib = apbv.load_library()
+    ws = apbv.apbv_query_attention_workspace_bytes
+    assert ws(1, 24, 128, 256, 64 * 1024, 1) == 0                       # one range: the plain kernel, no workspace
+    per_split = 256 * 24 * 128 * 2 + 256 * 24 * 4                       # bf16 partial + fp32 lse, already 256-aligned
+    assert ws(1, 24, 128, 256, 64 * 1024, 8) == 8 * per_split
+    assert ws(1, 24, 128, 256, 64 * 1024, 100000) == 256 * per_split    # clipped to 256 ranges
+    assert ws(1, 24, 128, 256, 100, 8) == 2 * per_split                 # two 64-key tiles only
+    auto = ws(1, 24, 128, 256, 64 * 1024, 0)
+    assert auto % per_split == 0 and 2 <= auto // per_split <= 256      # a short block over a long context is split
+    assert ws(1, 24, 128, 16384, 64 * 1024, 0) == 0                     # a full block fills the GPU by itself
+    assert ws(0, 24, 128, 256, 1024, 0) == 0 and ws(1, 24, 96, 256, 1024, 0) == 0 and ws(1, 24, 128, 256, 1024, -1) == 0
+
+    def call(n_splits=4, ws_ptr=0x100000, ws_bytes=1 << 30, out=0x2000, n_q=64, l_a=4096, hq=4):
+        e = view(0, 2, 128)
+        return lib.apbv_query_attention(1, hq, 2, 128, view(n_q, hq, 128), view(l_a, 2, 128), view(l_a, 2, 128),
+                                        e, e, e, e, 0.1, n_splits, out, None, ws_ptr, ws_bytes, None)
+    assert call(ws_ptr=None) == -4 and call(ws_ptr=0x100010) == -4 and call(ws_bytes=1024) == -4
+    assert call(n_splits=-1) == -2 and call(out=None) == -1 and call(hq=3) == -2 and call(n_q=0) == -2
 
 
 def test_product_path_has_no_oracle_or_cpu_fallback():
