@@ -139,6 +139,34 @@ apbv_status apbv_merge_lse(int n_parts, int64_t rows, int n_q_heads, int head_di
                            const float* parts_lse, int64_t part_stride_lse,
                            void* out, float* lse_out, void* hip_stream);
 
+/*
+ * One attention problem of a group: the arguments of apbv_host_attention for batch 1.
+ */
+typedef struct {
+  apbv_tensor q_local;
+  apbv_tensor k_anchor, v_anchor;
+  apbv_tensor k_pass, v_pass;
+  apbv_tensor k_local, v_local;   /* must hold q_local.tokens tokens (a causal segment) */
+  void* out;                      /* [L, Hq, d] bf16 */
+  float* lse_out;                 /* optional [Hq, L] fp32 */
+} apbv_attention_item;
+
+/*
+ * A physical host's attention work of one layer in ONE launch (Alg. 1 "context attention" of both virtual hosts,
+ * Sec. 4.3; and the anchor block's own causal attention): n_items independent problems with the same head counts and
+ * head_dim but their own lengths -- for host h of H the blocks h and 2H-1-h see h*l_p and (2H-1-h)*l_p passing keys,
+ * the anchor block is a problem with no anchor and no passing segment.  Every problem computes exactly what
+ * apbv_host_attention computes for it (bit-identical results); the launch orders the query tiles of all problems
+ * together, heaviest first, so that the short problems fill the tail of the long one.
+ *
+ *   items     HOST array of n_items descriptors (read during the call only); 1 <= n_items <= 8
+ * Errors as for apbv_host_attention, for any item; a problem without a causal segment is APBV_ERR_UNSUPPORTED here.
+ * Outputs of different items must not overlap.
+ */
+apbv_status apbv_host_attention_group(int n_items, const apbv_attention_item* items,
+                                      int n_q_heads, int n_kv_heads, int head_dim,
+                                      float softmax_scale, void* hip_stream);
+
 /* Host, pure.  Bytes of workspace apbv_query_attention needs (256-byte aligned; 0 when the call would not split
  * the keys, and 0 on invalid arguments).  n_keys = l_a + n_p + local keys; n_splits as passed to the call. */
 size_t apbv_query_attention_workspace_bytes(int batch, int n_q_heads, int head_dim, int64_t n_q, int64_t n_keys,

@@ -6,10 +6,12 @@ library; the first call does, and raises if it has not been built.
 """
 from .binding import (  # noqa: F401
     ApbvError,
+    ApbvAttentionItem,
     ApbvTensor,
     apbv_compress_kv,
     apbv_compress_workspace_bytes,
     apbv_host_attention,
+    apbv_host_attention_group,
     apbv_merge_lse,
     apbv_query_attention,
     apbv_query_attention_workspace_bytes,

@@ -33,6 +33,18 @@ class ApbvTensor(ctypes.Structure):
     ]
 
 
+class ApbvAttentionItem(ctypes.Structure):
+    """Mirror of ``apbv_attention_item`` in include/apbv.h."""
+    _fields_ = [
+        ("q_local", ApbvTensor),
+        ("k_anchor", ApbvTensor), ("v_anchor", ApbvTensor),
+        ("k_pass", ApbvTensor), ("v_pass", ApbvTensor),
+        ("k_local", ApbvTensor), ("v_local", ApbvTensor),
+        ("out", ctypes.c_void_p),
+        ("lse_out", ctypes.c_void_p),
+    ]
+
+
 def load_library() -> ctypes.CDLL:
     """Load libapbv.so (built in-tree by ``paper_2601_21444_amd.build``); raises if it is missing."""
     global _lib
@@ -74,6 +86,10 @@ def load_library() -> ctypes.CDLL:
         ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor, ApbvTensor,
         ctypes.c_float, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.apbv_host_attention_group.restype = ctypes.c_int
+    lib.apbv_host_attention_group.argtypes = [
+        ctypes.c_int, ctypes.POINTER(ApbvAttentionItem), ctypes.c_int, ctypes.c_int, ctypes.c_int,
+        ctypes.c_float, ctypes.c_void_p]
     _lib = lib
     return lib
 
@@ -186,6 +202,48 @@ def apbv_host_attention(q_local: torch.Tensor, k_anchor: torch.Tensor, v_anchor:
         out = out[0] if out.dim() == 4 else out
         lse_out = lse_out[0] if (lse_out is not None and lse_out.dim() == 3) else lse_out
     return (out, lse_out) if return_lse else out
+
+
+def apbv_host_attention_group(problems, softmax_scale: float, *, return_lse: bool = False,
+                              stream: Optional[torch.cuda.Stream] = None):
+    """Several unbatched attention problems in one launch; see apbv_host_attention_group in include/apbv.h.
+    ``problems`` is a sequence of ``(q_local, k_anchor, v_anchor, k_pass, v_pass, k_local, v_local)`` tuples of
+    ``[tokens, heads, d]`` tensors (optionally followed by preallocated ``out`` and ``lse_out``).  Returns the list of
+    outputs (of ``(out, lse)`` pairs with ``return_lse``)."""
+    lib = load_library()
+    n = len(problems)
+    items = (ApbvAttentionItem * max(n, 1))()
+    results = []
+    hq = hkv = d = 0
+    for m, prob in enumerate(problems):
+        tensors = prob[:7]
+        out = prob[7] if len(prob) > 7 else None
+        lse = prob[8] if len(prob) > 8 else None
+        views = []
+        for t in tensors:
+            if t.dim() != 3:
+                raise ValueError("group problems are unbatched [tokens, heads, d] tensors")
+            views.append(tensor_view(t)[0])
+        q = tensors[0]
+        L, hq_m, d_m = q.shape
+        hkv_m = tensors[1].shape[-2]
+        if m == 0:
+            hq, hkv, d = hq_m, hkv_m, d_m
+        elif (hq_m, hkv_m, d_m) != (hq, hkv, d):
+            raise ValueError("all problems of a group share the head counts and head_dim")
+        if out is None:
+            out = torch.empty((L, hq, d), dtype=torch.bfloat16, device=q.device)
+        if return_lse and lse is None:
+            lse = torch.empty((hq, L), dtype=torch.float32, device=q.device)
+        it = items[m]
+        (it.q_local, it.k_anchor, it.v_anchor, it.k_pass, it.v_pass, it.k_local, it.v_local) = views
+        it.out = out.data_ptr()
+        it.lse_out = lse.data_ptr() if lse is not None else None
+        results.append((out, lse) if return_lse else out)
+    st = lib.apbv_host_attention_group(n, items, hq, hkv, d, float(softmax_scale), _stream_ptr(stream))
+    if st != 0:
+        raise ApbvError(st, "apbv_host_attention_group")
+    return results
 
 
 def apbv_query_attention_workspace_bytes(batch: int, n_q_heads: int, head_dim: int, n_q: int, n_keys: int,

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "apbv.h"
+#include "attention_schedule.h"
 
 namespace apbv {
 
@@ -56,6 +57,15 @@ constexpr int kAttnKeyTile = 64;      // keys per tile of the attention kernel
 constexpr int kAttnQueryTile = 256;   // query rows per workgroup
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream);
+
+// Several attention problems (batch 1, one key range each, same head counts) in one launch.  The caller fills
+// item[] and n_items; the launcher fills the schedule.
+struct AttnGroupParams {
+  AttnParams item[kMaxGroupItems];
+  GroupSchedule sched;
+  int n_items;
+};
+apbv_status launch_host_attention_group(AttnGroupParams& gp, int head_dim, hipStream_t stream);
 
 // ---- merge of partial attention results -------------------------------------------------------
 struct MergeParams {

@@ -180,6 +180,23 @@ apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int he
   return launch_host_attention(p, head_dim, static_cast<hipStream_t>(hip_stream));
 }
 
+apbv_status apbv_host_attention_group(int n_items, const apbv_attention_item* items, int n_q_heads, int n_kv_heads,
+                                      int head_dim, float softmax_scale, void* hip_stream) {
+  if (n_items < 1 || n_items > kMaxGroupItems) return APBV_ERR_SHAPE;
+  if (items == nullptr) return APBV_ERR_NULL;
+  AttnGroupParams gp;
+  for (int m = 0; m < n_items; ++m) {
+    const apbv_attention_item& it = items[m];
+    const apbv_status st = fill_attention(1, n_q_heads, n_kv_heads, head_dim, it.q_local, it.k_anchor, it.v_anchor,
+                                          it.k_pass, it.v_pass, it.k_local, it.v_local, softmax_scale, it.out,
+                                          it.lse_out, gp.item[m]);
+    if (st != APBV_OK) return st;
+    if (it.k_local.tokens != it.q_local.tokens) return APBV_ERR_UNSUPPORTED;   // the merged schedule assumes a causal segment
+  }
+  gp.n_items = n_items;
+  return launch_host_attention_group(gp, head_dim, static_cast<hipStream_t>(hip_stream));
+}
+
 size_t apbv_query_attention_workspace_bytes(int batch, int n_q_heads, int head_dim, int64_t n_q, int64_t n_keys,
                                             int n_splits) {
   if (batch < 1 || n_q_heads < 1 || (head_dim != 64 && head_dim != 128) || n_q < 1 || n_keys < 1 || n_splits < 0 ||

@@ -182,27 +182,15 @@ struct TileStream {
   }
 };
 
+// One workgroup's work: query tile `qt` of query head (kvh, g) of batch item b, key range `split`.
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles,
-                                                                     const int n_items) {
+__device__ __forceinline__ void attention_workgroup(const AttnParams& p, const int qt, const int b, const int kvh,
+                                                    const int g, const int split) {
   using T = Tile<D>;
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[T::TILE_BYTES];
-
-  // ---- workgroup -> (query tile, head, batch); the heads of one KV group share an XCD
-  const int xcd = blockIdx.x % kXcds;
-  const int slot = blockIdx.x / kXcds;
-  const int item_split = (slot / p.group) * kXcds + xcd;
-  if (item_split >= n_items) return;
-  const int split = item_split % p.n_splits;     // key ranges of one item share nothing: spread them over the XCDs
-  const int item = item_split / p.n_splits;
-  const int g = slot % p.group;
-  const int bh = p.batch * p.hkv;
-  const int qt = n_qtiles - 1 - item / bh;       // heaviest query tiles first
-  const int b = (item % bh) / p.hkv;
-  const int kvh = (item % bh) % p.hkv;
   const int h = kvh * p.group + g;
 
   const int tid = threadIdx.x;
@@ -429,6 +417,42 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   }
 }
 
+// ---- workgroup -> (query tile, head, batch, key range); the heads of one KV group share an XCD
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles,
+                                                                     const int n_items) {
+  const int xcd = blockIdx.x % kXcds;
+  const int slot = blockIdx.x / kXcds;
+  const int item_split = (slot / p.group) * kXcds + xcd;
+  if (item_split >= n_items) return;
+  const int split = item_split % p.n_splits;     // key ranges of one item share nothing: spread them over the XCDs
+  const int item = item_split / p.n_splits;
+  const int g = slot % p.group;
+  const int bh = p.batch * p.hkv;
+  const int qt = n_qtiles - 1 - item / bh;       // heaviest query tiles first
+  const int b = (item % bh) / p.hkv;
+  const int kvh = (item % bh) % p.hkv;
+  attention_workgroup<D>(p, qt, b, kvh, g, split);
+}
+
+// ---- several attention problems of different lengths in one launch (the two virtual hosts and the anchor
+// block of a physical host, Alg. 1 / Sec. 4.3): one workgroup per entry of the merged heaviest-first order of
+// all (problem, query tile) pairs, per KV head and group member.
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void host_attention_group_kernel(const AttnGroupParams gp) {
+  const int group = gp.item[0].group, hkv = gp.item[0].hkv;
+  const int xcd = blockIdx.x % kXcds;
+  const int slot = blockIdx.x / kXcds;
+  const int unit = (slot / group) * kXcds + xcd;
+  if (unit >= gp.sched.n_entries * hkv) return;
+  const int g = slot % group;
+  const int entry = unit / hkv, kvh = unit % hkv;
+  int m, qt;
+  decode_group_entry(gp.sched, entry, m, qt);
+  if (m >= gp.n_items || qt < 0 || (int64_t)qt * kBM >= gp.item[m].L) return;      // never taken for a schedule the launcher built
+  attention_workgroup<D>(gp.item[m], qt, 0, kvh, g, 0);
+}
+
 }  // namespace
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream) {
@@ -442,6 +466,33 @@ apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t
     hipLaunchKernelGGL(host_attention_kernel<128>, grid, block, 0, stream, p, n_qtiles, (int)n_items);
   else if (head_dim == 64)
     hipLaunchKernelGGL(host_attention_kernel<64>, grid, block, 0, stream, p, n_qtiles, (int)n_items);
+  else
+    return APBV_ERR_UNSUPPORTED;
+  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+}
+
+apbv_status launch_host_attention_group(AttnGroupParams& gp, int head_dim, hipStream_t stream) {
+  static_assert(kGroupQueryTile == kBM, "the schedule's query tile is the kernel's");
+  static_assert(sizeof(AttnGroupParams) <= 4096, "kernel arguments are limited to 4 KB");
+  const int n = gp.n_items;
+  if (n < 1 || n > kMaxGroupItems) return APBV_ERR_UNSUPPORTED;
+  int64_t n_vis[kMaxGroupItems], rows[kMaxGroupItems];
+  for (int m = 0; m < n; ++m) {
+    n_vis[m] = gp.item[m].n_vis;
+    rows[m] = gp.item[m].L;
+  }
+  if (!build_group_schedule(n, n_vis, rows, gp.sched)) return APBV_ERR_UNSUPPORTED;
+  const int64_t first = gp.sched.n_entries;
+  const AttnParams& p0 = gp.item[0];
+  const int64_t n_units = first * p0.hkv;
+  const int64_t n_blocks = (n_units + kXcds - 1) / kXcds * kXcds * p0.group;
+  if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
+  dim3 grid((unsigned)n_blocks);
+  dim3 block(kThreads);
+  if (head_dim == 128)
+    hipLaunchKernelGGL(host_attention_group_kernel<128>, grid, block, 0, stream, gp);
+  else if (head_dim == 64)
+    hipLaunchKernelGGL(host_attention_group_kernel<64>, grid, block, 0, stream, gp);
   else
     return APBV_ERR_UNSUPPORTED;
   return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;

@@ -63,6 +63,20 @@ __device__ __forceinline__ double bf16_to_f64(uint32_t bits16) {
   return (double)__uint_as_float(bits16 << 16);
 }
 
+// A float64 moved across lanes by a DPP control (two 32-bit moves).  Controls: exchanges inside a quad, and
+// rotations of a 16-lane row (lane i reads lane i-n of its row).
+constexpr int kDppXor1 = 0xB1;    // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;    // quad_perm [2,3,0,1]
+constexpr int kDppRor4 = 0x124;   // row_ror:4
+constexpr int kDppRor8 = 0x128;   // row_ror:8
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xf, 0xf, false);
+  hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+
 // ------------------------------------------------------------------------------------------------
 // q_bar[b, v, c] = sum_g sum_t Q_qr[b, t, v*G+g, c]   (float64; the addends are bf16 so the sum is
 // exact or within an ulp whatever the order).  One workgroup per (KV head, batch item): D/8 lanes per
@@ -117,6 +131,7 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
   constexpr int LPR = D / 8;               // lanes per row
   constexpr int RPS = 256 / LPR;           // rows per step of the workgroup
   constexpr int UNROLL = 4;
+  static_assert(LPR == 8 || LPR == 16, "the cross-lane reduction below is written for 8 or 16 lanes per row");
   const int v = blockIdx.y, b = blockIdx.z;
   const int c = threadIdx.x % LPR;
   const int rsub = threadIdx.x / LPR;
@@ -138,6 +153,7 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
       if (j < r_end) z = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + j * k.st));
       x[u] = z;
     }
+    double a[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       double acc = 0.0;
@@ -146,13 +162,24 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
         acc = __builtin_fma(qv[2 * e], bf16_to_f64(x[u][e] & 0xffffu), acc);
         acc = __builtin_fma(qv[2 * e + 1], bf16_to_f64(x[u][e] >> 16), acc);
       }
-#pragma unroll
-      for (int m = 1; m < LPR; m <<= 1) acc += __shfl_xor(acc, m);
-      const int64_t j = r0 + u * RPS + rsub;
-      if (c == 0 && j < r_end) {
-        s_ws[out_base + j] = acc;
-        if (s_out) s_out[out_base + j] = acc;
-      }
+      a[u] = acc;
+    }
+    // Reduce the four rows over the row's lanes as a reduce-scatter: after the two exchanges inside a quad each
+    // lane holds one row's sum over its quad, two rotations by 4 and 8 lanes finish it.  Every row takes the same
+    // summation tree (the adds commute), so identical rows get identical scores.
+    const bool odd1 = (c & 1) != 0, odd2 = (c & 2) != 0;
+    double keep0 = odd1 ? a[2] : a[0], keep1 = odd1 ? a[3] : a[1];
+    keep0 += dpp_f64<kDppXor1>(odd1 ? a[0] : a[2]);
+    keep1 += dpp_f64<kDppXor1>(odd1 ? a[1] : a[3]);
+    double acc = odd2 ? keep1 : keep0;
+    acc += dpp_f64<kDppXor2>(odd2 ? keep0 : keep1);
+    acc += dpp_f64<kDppRor4>(acc);
+    if (LPR == 16) acc += dpp_f64<kDppRor8>(acc);
+    const int u = (odd1 ? 2 : 0) + (odd2 ? 1 : 0);     // the row this lane ended up with
+    const int64_t j = r0 + u * RPS + rsub;
+    if (c >= LPR - 4 && j < r_end) {                   // the last quad of the row's lanes holds complete sums
+      s_ws[out_base + j] = acc;
+      if (s_out) s_out[out_base + j] = acc;
     }
   }
 }

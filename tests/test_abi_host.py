@@ -21,7 +21,8 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = apbv.load_library()
     names = declared_symbols()
-    assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_merge_lse",
+    assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_host_attention_group",
+                     "apbv_merge_lse",
                      "apbv_query_attention", "apbv_query_attention_workspace_bytes", "apbv_status_string",
                      "apbv_version"]
     for n in names:
@@ -126,6 +127,29 @@ def test_query_attention_workspace_plan_and_rejections():
     assert call(n_splits=-1) == -2 and call(out=None) == -1 and call(hq=3) == -2 and call(n_q=0) == -2
 
 
+def test_attention_group_rejects_bad_arguments_without_launching():
+    lib = apbv.load_library()
+
+    def item(L=64, l_a=8, n_p=16, local=None, out=0x2000):
+        it = apbv.ApbvAttentionItem()
+        it.q_local = view(L, 4, 128)
+        it.k_anchor = it.v_anchor = view(l_a, 2, 128)
+        it.k_pass = it.v_pass = view(n_p, 2, 128)
+        it.k_local = it.v_local = view(L if local is None else local, 2, 128)
+        it.out, it.lse_out = out, None
+        return it
+
+    def call(items, n=None, hq=4, hkv=2, d=128, scale=0.1):
+        arr = (apbv.ApbvAttentionItem * max(len(items), 1))(*items)
+        return lib.apbv_host_attention_group(len(items) if n is None else n, arr, hq, hkv, d, scale, None)
+    assert call([], n=0) == -2 and call([item()] * 9) == -2
+    assert lib.apbv_host_attention_group(1, None, 4, 2, 128, 0.1, None) == -1
+    assert call([item(), item(out=None)]) == -1
+    assert call([item(), item(local=0)]) == -3              # no causal segment: not in a group
+    assert call([item(), item(local=63)]) == -2
+    assert call([item()], hq=3) == -2 and call([item()], d=96) == -3 and call([item()], scale=-1.0) == -2
+
+
 def test_product_path_has_no_oracle_or_cpu_fallback():
     """The package must not import the oracle, and must raise when the library is absent."""
     pkg = os.path.join(ROOT, "paper_2601_21444_amd")
@@ -142,3 +166,14 @@ def test_product_path_has_no_oracle_or_cpu_fallback():
             b.load_library()
     finally:
         b._lib, b._LIB_PATH = saved_lib, saved_path
+
+
+def test_group_schedule_covers_every_query_tile_once(tmp_path):
+    """The merged heaviest-first schedule of apbv_host_attention_group, checked by brute force on the host."""
+    import subprocess
+    exe = tmp_path / "schedule_check"
+    src = os.path.join(ROOT, "tests", "host", "schedule_check.cpp")
+    inc = os.path.join(ROOT, "paper_2601_21444_amd", "csrc")
+    subprocess.run(["g++", "-O1", "-std=c++17", "-Wall", "-I", inc, src, "-o", str(exe)], check=True)
+    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert res.returncode == 0 and "schedule ok" in res.stdout, res.stdout + res.stderr
