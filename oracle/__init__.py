@@ -7,6 +7,9 @@ from .apbv_oracle import (  # noqa: F401
     bf16_bits_to_f64,
     pooled_query,
     importance_scores,
+    importance_scores_max,
+    importance_scores_softmax_sum,
+    logit_matrix,
     arg_top,
     compress_kv,
     make_passing_block,

@@ -5,7 +5,8 @@ shares no code with the HIP path and must never be imported by it.
 
 What the paper fixes, and what each function follows:
 
-* ``importance_scores`` / ``arg_top`` / ``compress_kv`` -- Sec. 3.3 "Approximate Attention" (the
+* ``importance_scores`` (and the alternative reductions ``importance_scores_max`` /
+  ``importance_scores_softmax_sum`` over ``logit_matrix``) / ``arg_top`` / ``compress_kv`` -- Sec. 3.3 "Approximate Attention" (the
   query-to-context scores Q_qr K^(h)T identify the l_p most important KV pairs) and Alg. 1, steps
   "Identify Essential KVs" and "Send Block 1's Essential KVs" (S_h <- Q_qr K^(h)T;
   (K,V).gather(ArgTop_{l_p}(S_h))).
@@ -76,6 +77,44 @@ def importance_scores(q_probe: np.ndarray, k: np.ndarray) -> np.ndarray:
     return s
 
 
+def logit_matrix(q_probe: np.ndarray, k: np.ndarray, kv_head: int) -> np.ndarray:
+    """The rows of S_h = Q_qr K^(h)T (Alg. 1) that belong to KV head ``kv_head``: raw logits
+    ``[n_q * G, L]`` float64, row (t, g) = Q_qr[t, kv_head*G+g, :] . K[:, kv_head, :]."""
+    q = bf16_bits_to_f64(q_probe)
+    kk = bf16_bits_to_f64(k)
+    n_q, hq, d = q.shape
+    hkv = kk.shape[1]
+    if hq % hkv:
+        raise ValueError("Hq must be a multiple of Hkv")
+    g = hq // hkv
+    rows = q[:, kv_head * g:(kv_head + 1) * g, :].reshape(n_q * g, d)
+    return rows @ kk[:, kv_head, :].T
+
+
+def importance_scores_max(q_probe: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """Alternative reduction of S_h to one score per key: s[v, j] = max over the query-block rows t and the
+    group's query heads g of the raw logit Q_qr[t, v*G+g, :] . K[j, v, :].  Returns float64 ``[Hkv, L]``.
+    (A reading of Sec. 3.3 / Alg. 1 other than the sum; **parity unpinned** by the paper like the sum.)"""
+    hkv = k.shape[1]
+    return np.stack([logit_matrix(q_probe, k, v).max(axis=0) for v in range(hkv)])
+
+
+def importance_scores_softmax_sum(q_probe: np.ndarray, k: np.ndarray, softmax_scale: float) -> np.ndarray:
+    """Alternative reduction of S_h: every query row's scaled logits are normalised by a softmax over the
+    block's keys (Eq. 1 without a mask) and the probabilities are summed over the rows:
+    s[v, j] = sum_{t, g} softmax_j(softmax_scale * S_h[(t, g), :])[j]  -- the attention mass the query block
+    puts on key j (the kind of pruning score App. C names for the FastV baseline, "SnapKV-like").  Returns float64
+    ``[Hkv, L]``.  **parity unpinned** by the paper."""
+    hkv = k.shape[1]
+    out = []
+    for v in range(hkv):
+        z = softmax_scale * logit_matrix(q_probe, k, v)
+        z = z - z.max(axis=1, keepdims=True)
+        e = np.exp(z)
+        out.append((e / e.sum(axis=1, keepdims=True)).sum(axis=0))
+    return np.stack(out)
+
+
 def arg_top(scores: np.ndarray, l_p: int) -> np.ndarray:
     """Indices of the l_p largest entries of a 1-D score vector, by descending score; equal scores by
     ascending index (a stable sort of 0..L-1 on the negated score)."""
@@ -90,9 +129,11 @@ def arg_top(scores: np.ndarray, l_p: int) -> np.ndarray:
     return order[:l_p].astype(np.int32)
 
 
-def compress_kv(q_probe: np.ndarray, k: np.ndarray, v: np.ndarray, l_p: int
+def compress_kv(q_probe: np.ndarray, k: np.ndarray, v: np.ndarray, l_p: int, reducer: str = "sum",
+                softmax_scale: Optional[float] = None
                 ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
-    """Compressed block of one context block (Alg. 1: (K,V).gather(ArgTop_{l_p}(S_h))).
+    """Compressed block of one context block (Alg. 1: (K,V).gather(ArgTop_{l_p}(S_h))).  ``reducer`` picks how
+    S_h becomes one score per key: "sum" (the adopted reading), "max" or "softmax_sum" (needs ``softmax_scale``).
 
     Returns ``(idx [Hkv, l_p] int32, K_c [l_p, Hkv, d] uint16, V_c [l_p, Hkv, d] uint16,
     scores [Hkv, L] float64)``; row i of K_c for head v is the bit copy of K[idx[v, i], v, :]."""
@@ -101,7 +142,16 @@ def compress_kv(q_probe: np.ndarray, k: np.ndarray, v: np.ndarray, l_p: int
     L, hkv, d = k.shape
     if v.shape != k.shape:
         raise ValueError("K and V must have the same shape")
-    s = importance_scores(q_probe, k)
+    if reducer == "sum":
+        s = importance_scores(q_probe, k)
+    elif reducer == "max":
+        s = importance_scores_max(q_probe, k)
+    elif reducer == "softmax_sum":
+        if softmax_scale is None:
+            raise ValueError("softmax_sum needs softmax_scale")
+        s = importance_scores_softmax_sum(q_probe, k, softmax_scale)
+    else:
+        raise ValueError("unknown reducer")
     idx = np.empty((hkv, l_p), dtype=np.int32)
     k_c = np.empty((l_p, hkv, d), dtype=np.uint16)
     v_c = np.empty((l_p, hkv, d), dtype=np.uint16)

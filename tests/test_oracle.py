@@ -343,6 +343,102 @@ def test_identical_key_rows_get_identical_scores():
     assert s[0, 200] == s[0, 3] == s[0, 256]
 
 
+# ------------------------------------------------------------------ alternative score reductions (max, softmax-sum)
+
+def brute_logits(qp, k, v, g):
+    """Pure-Python raw logits of KV head v: rows ordered (t, g)."""
+    q, kk = to_lists(qp), to_lists(k)
+    return [[math.fsum(q[t][v * g + gg][c] * kk[j][v][c] for c in range(len(kk[0][0]))) for j in range(len(kk))]
+            for t in range(len(q)) for gg in range(g)]
+
+
+def test_alternative_reductions_match_pure_python_bruteforce():
+    rng = np.random.default_rng(41)
+    n_q, hq, hkv, d, L = 3, 4, 2, 8, 11
+    g = hq // hkv
+    qp, k = rand_bits(rng, (n_q, hq, d)), rand_bits(rng, (L, hkv, d))
+    scale = 0.3
+    s_max = oracle.importance_scores_max(qp, k)
+    s_sm = oracle.importance_scores_softmax_sum(qp, k, scale)
+    for v in range(hkv):
+        S = brute_logits(qp, k, v, g)
+        assert len(S) == n_q * g
+        np.testing.assert_allclose(oracle.logit_matrix(qp, k, v), np.array(S), rtol=1e-13, atol=1e-13)
+        for j in range(L):
+            assert abs(s_max[v, j] - max(row[j] for row in S)) <= 1e-12
+            mass = 0.0
+            for row in S:
+                m = max(row)
+                w = [math.exp(scale * (z - m)) for z in row]
+                mass += w[j] / math.fsum(w)
+            assert abs(s_sm[v, j] - mass) <= 1e-12
+
+
+def test_softmax_sum_closed_forms():
+    rng = np.random.default_rng(42)
+    n_q, hq, hkv, d, L = 5, 6, 2, 16, 40
+    qp = rand_bits(rng, (n_q, hq, d))
+    # every row's probabilities sum to one: the scores of a head sum to the number of rows n_q * G
+    k = rand_bits(rng, (L, hkv, d))
+    s = oracle.importance_scores_softmax_sum(qp, k, 0.25)
+    np.testing.assert_allclose(s.sum(axis=1), n_q * (hq // hkv), rtol=1e-12)
+    assert np.all(s > 0)
+    # identical keys: uniform attention, every key gets (n_q * G) / L
+    k_same = np.repeat(k[:1], L, axis=0)
+    np.testing.assert_allclose(oracle.importance_scores_softmax_sum(qp, k_same, 0.25), n_q * (hq // hkv) / L, rtol=1e-12)
+    # the library softmax over the key axis, one row at a time
+    for v in range(hkv):
+        S = oracle.logit_matrix(qp, k, v)
+        ref = sum(scipy.special.softmax(0.25 * S[r]) for r in range(S.shape[0]))
+        np.testing.assert_allclose(s[v], ref, rtol=1e-12)
+    # a large scale turns the softmax into a count of each key's row-wise wins (no ties in random data)
+    s_hard = oracle.importance_scores_softmax_sum(qp, k, 1e4)
+    for v in range(hkv):
+        wins = np.bincount(oracle.logit_matrix(qp, k, v).argmax(axis=1), minlength=L)
+        np.testing.assert_allclose(s_hard[v], wins, atol=1e-9)
+
+
+def test_max_reduction_special_cases():
+    rng = np.random.default_rng(43)
+    d, L = 16, 50
+    k = rand_bits(rng, (L, 1, d))
+    # one probe row, one head: all three raw reductions of a single row coincide with that row
+    q1 = rand_bits(rng, (1, 1, d))
+    np.testing.assert_allclose(oracle.importance_scores_max(q1, k), oracle.importance_scores(q1, k), rtol=1e-13, atol=1e-13)
+    # repeating probe rows leaves the max unchanged (the sum doubles) and row order is irrelevant
+    q = rand_bits(rng, (6, 2, d))
+    s = oracle.importance_scores_max(q, k)
+    np.testing.assert_array_equal(oracle.importance_scores_max(np.concatenate([q, q]), k), s)
+    np.testing.assert_array_equal(oracle.importance_scores_max(q[::-1], k), s)
+    np.testing.assert_allclose(oracle.importance_scores(np.concatenate([q, q]), k), 2 * oracle.importance_scores(q, k), rtol=1e-13)
+    # the max dominates the mean of the rows, and is attained by some row
+    S = oracle.logit_matrix(q, k, 0)
+    assert np.all(s[0] >= oracle.importance_scores(q, k)[0] / S.shape[0] - 1e-12)
+    assert np.all((S == s[0][None, :]).any(axis=0))
+    # heads are grouped: KV head 1 of a 4-head probe uses query heads 2 and 3 only
+    q4, k2 = rand_bits(rng, (3, 4, d)), rand_bits(rng, (L, 2, d))
+    qf, kf = wl.bf16_bits_to_f32(q4).astype(np.float64), wl.bf16_bits_to_f32(k2).astype(np.float64)
+    want = np.maximum((qf[:, 2] @ kf[:, 1].T).max(axis=0), (qf[:, 3] @ kf[:, 1].T).max(axis=0))
+    np.testing.assert_allclose(oracle.importance_scores_max(q4, k2)[1], want, rtol=1e-13, atol=1e-13)
+
+
+def test_compress_with_alternative_reducers_selects_by_their_scores():
+    rng = np.random.default_rng(44)
+    qp, k, v = rand_bits(rng, (4, 4, 16)), rand_bits(rng, (60, 2, 16)), rand_bits(rng, (60, 2, 16))
+    for reducer, scores in (("max", oracle.importance_scores_max(qp, k)),
+                            ("softmax_sum", oracle.importance_scores_softmax_sum(qp, k, 0.25))):
+        idx, k_c, v_c, s = oracle.compress_kv(qp, k, v, 7, reducer=reducer, softmax_scale=0.25)
+        np.testing.assert_array_equal(s, scores)
+        for h in range(2):
+            np.testing.assert_array_equal(idx[h], oracle.arg_top(scores[h], 7))
+            np.testing.assert_array_equal(k_c[:, h], k[idx[h], h])
+            np.testing.assert_array_equal(v_c[:, h], v[idx[h], h])
+    with pytest.raises(ValueError):
+        oracle.compress_kv(qp, k, v, 7, reducer="softmax_sum")
+    with pytest.raises(ValueError):
+        oracle.compress_kv(qp, k, v, 7, reducer="median")
+
+
 # ------------------------------------------------------------------ ArgTop / gather pins
 
 with open(os.path.join(GOLDEN, "handworked_argtop.json")) as f:
