@@ -94,6 +94,34 @@ apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_
                              void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * How the n_q*G x L score matrix S_h = Q_qr K^(h)T of Alg. 1 becomes one score per key and KV head (the paper does
+ * not say; the sum is the reading this library adopts, the others are offered so that a caller can match another):
+ *   APBV_REDUCE_SUM          s[j] = sum over rows (t, g) of S[(t, g), j]          (apbv_compress_kv; float64)
+ *   APBV_REDUCE_MAX          s[j] = max over rows of S[(t, g), j]
+ *   APBV_REDUCE_SOFTMAX_SUM  s[j] = sum over rows of softmax_j(softmax_scale * S[(t, g), :])[j], the attention mass
+ *                            the query block puts on key j (softmax over the block's L keys, no mask)
+ * MAX and SOFTMAX_SUM form the logits on the matrix cores: bf16 operands, fp32 accumulation and reduction; the
+ * scores are then widened to float64 and ranked exactly as in apbv_compress_kv (ties by ascending index).
+ */
+typedef enum { APBV_REDUCE_SUM = 0, APBV_REDUCE_MAX = 1, APBV_REDUCE_SOFTMAX_SUM = 2 } apbv_reducer;
+
+/* Host, pure.  Bytes of workspace apbv_compress_kv_reduced needs (0 on invalid arguments); 256-byte aligned. */
+size_t apbv_compress_reduced_workspace_bytes(int reducer, int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                                             int64_t n_q, int64_t L, int64_t l_p);
+
+/*
+ * apbv_compress_kv with a chosen reduction (Sec. 3.3 / Alg. 1, same outputs and layouts).  `reducer` is an
+ * apbv_reducer; `softmax_scale` is used by APBV_REDUCE_SOFTMAX_SUM only (finite, positive) and ignored otherwise.
+ * With APBV_REDUCE_SUM the call is apbv_compress_kv.  APBV_REDUCE_SOFTMAX_SUM supports up to 8192 rows n_q*G.
+ */
+apbv_status apbv_compress_kv_reduced(int reducer, float softmax_scale,
+                                     int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                                     apbv_tensor q_probe, apbv_tensor k_local, apbv_tensor v_local,
+                                     int64_t l_p,
+                                     int32_t* idx_out, void* k_c_out, void* v_c_out, double* scores_out,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Fused host attention (Eq. 4 by the definition of Eq. 1):
  *   O[i, h, :] = sum_j softmax_j( softmax_scale * Q[i, h, :] . Kcat[j, h/G, :] + mask(i, j) ) Vcat[j, h/G, :]
  * over Kcat = [K_a ; K_p ; K], Vcat = [V_a ; V_p ; V]; mask = 0 for anchor and passing keys; local key

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     ApbvAttentionItem,
     ApbvTensor,
     apbv_compress_kv,
+    apbv_compress_reduced_workspace_bytes,
     apbv_compress_workspace_bytes,
     apbv_host_attention,
     apbv_host_attention_group,

@@ -67,6 +67,11 @@ def load_library() -> ctypes.CDLL:
         ApbvTensor, ApbvTensor, ApbvTensor, ctypes.c_int64,
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.apbv_compress_reduced_workspace_bytes.restype = ctypes.c_size_t
+    lib.apbv_compress_reduced_workspace_bytes.argtypes = [
+        ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
+    lib.apbv_compress_kv_reduced.restype = ctypes.c_int
+    lib.apbv_compress_kv_reduced.argtypes = [ctypes.c_int, ctypes.c_float] + list(lib.apbv_compress_kv.argtypes)
     lib.apbv_host_attention.restype = ctypes.c_int
     lib.apbv_host_attention.argtypes = [
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -126,13 +131,24 @@ def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
     return int(s.cuda_stream)
 
 
+REDUCERS = {"sum": 0, "max": 1, "softmax_sum": 2}
+
+
+def apbv_compress_reduced_workspace_bytes(reducer: str, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                                          n_q: int, L: int, l_p: int) -> int:
+    return int(load_library().apbv_compress_reduced_workspace_bytes(REDUCERS[reducer], batch, n_q_heads, n_kv_heads,
+                                                                    head_dim, n_q, L, l_p))
+
+
 def apbv_compress_kv(q_probe: torch.Tensor, k_local: torch.Tensor, v_local: torch.Tensor, l_p: int, *,
+                     reducer: str = "sum", softmax_scale: float = 0.0,
                      return_scores: bool = False, workspace: Optional[torch.Tensor] = None,
                      idx_out: Optional[torch.Tensor] = None, k_c_out: Optional[torch.Tensor] = None,
                      v_c_out: Optional[torch.Tensor] = None, scores_out: Optional[torch.Tensor] = None,
                      stream: Optional[torch.cuda.Stream] = None):
     """Compressed block (idx, K_c, V_c[, scores]) of one context block; see apbv_compress_kv in
-    include/apbv.h.  Tensors are ``[tokens, heads, d]`` or batched ``[batch, tokens, heads, d]``."""
+    include/apbv.h.  Tensors are ``[tokens, heads, d]`` or batched ``[batch, tokens, heads, d]``.  A ``reducer``
+    other than "sum" ("max", "softmax_sum") goes through apbv_compress_kv_reduced."""
     lib = load_library()
     batched = k_local.dim() == 4
     qv, bq = tensor_view(q_probe)
@@ -152,10 +168,12 @@ def apbv_compress_kv(q_probe: torch.Tensor, k_local: torch.Tensor, v_local: torc
     if return_scores and scores_out is None:
         scores_out = torch.empty((b, hkv, L), dtype=torch.float64, device=dev)
     if workspace is None:
-        nbytes = max(apbv_compress_workspace_bytes(b, hkv, d, L, l_p), 256)
+        nbytes = max(apbv_compress_reduced_workspace_bytes(reducer, b, hq, hkv, d, q_probe.shape[-3], L, l_p), 256)
         workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
-    st = lib.apbv_compress_kv(
-        b, hq, hkv, d, qv, kv, vv, int(l_p),
+    entry = lib.apbv_compress_kv if reducer == "sum" else lib.apbv_compress_kv_reduced
+    lead = () if reducer == "sum" else (REDUCERS[reducer], float(softmax_scale))
+    st = entry(
+        *lead, b, hq, hkv, d, qv, kv, vv, int(l_p),
         idx_out.data_ptr() if l_p > 0 else None, k_c_out.data_ptr() if l_p > 0 else None,
         v_c_out.data_ptr() if l_p > 0 else None,
         scores_out.data_ptr() if scores_out is not None else None,

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libapbv.so")
-SOURCES = ["api.hip", "attention.hip", "compress.hip", "merge.hip"]
+SOURCES = ["api.hip", "attention.hip", "compress.hip", "merge.hip", "score_matrix.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

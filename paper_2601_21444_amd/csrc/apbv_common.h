@@ -93,9 +93,14 @@ struct CompressParams {
   double* scores_out;     // optional [batch, Hkv, L]
   void* workspace;
   size_t workspace_bytes;
+  int reducer;            // apbv_reducer: how the score matrix becomes one score per key
+  float scale_log2;       // softmax_scale * log2(e), for APBV_REDUCE_SOFTMAX_SUM
 };
 
+// workspace = [selection workspace | row statistics of the matrix reductions]
 size_t compress_workspace_bytes(int batch, int hkv, int d, int64_t L, int64_t l_p);
+size_t matrix_scores_workspace_bytes(int reducer, int batch, int hkv, int64_t n_rows, int64_t L);
 apbv_status launch_compress(const CompressParams& p, hipStream_t stream);
+apbv_status launch_matrix_scores(const CompressParams& p, double* scores, void* stats_ws, hipStream_t stream);
 
 }  // namespace apbv

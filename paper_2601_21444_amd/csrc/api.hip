@@ -105,6 +105,57 @@ KeySplit plan_key_split(int batch, int n_q_heads, int64_t n_q, int64_t n_keys, i
 
 size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
+size_t reduced_workspace_bytes(int reducer, int batch, int hq, int hkv, int d, int64_t n_q, int64_t L, int64_t l_p) {
+  const size_t base = compress_workspace_bytes(batch, hkv, d, L, l_p);
+  if (reducer == APBV_REDUCE_SUM) return base;
+  return (base + 255) / 256 * 256 + matrix_scores_workspace_bytes(reducer, batch, hkv, n_q * (hq / hkv), L);
+}
+
+apbv_status compress_entry(int reducer, float softmax_scale, int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_probe,
+                             apbv_tensor k_local, apbv_tensor v_local, int64_t l_p, int32_t* idx_out, void* k_c_out,
+                             void* v_c_out, double* scores_out, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
+  apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
+  if (st != APBV_OK) return st;
+  if ((st = check_view(q_probe, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
+  if (v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
+  const int64_t L = k_local.tokens;
+  if (l_p < 0 || l_p > L) return APBV_ERR_SHAPE;
+  if (l_p > 0) {
+    if (idx_out == nullptr || k_c_out == nullptr || v_c_out == nullptr) return APBV_ERR_NULL;
+    if (!aligned(k_c_out, 16) || !aligned(v_c_out, 16) || !aligned(idx_out, 4)) return APBV_ERR_SHAPE;
+  }
+  if (scores_out != nullptr && !aligned(scores_out, 8)) return APBV_ERR_SHAPE;
+  if (reducer != APBV_REDUCE_SUM && reducer != APBV_REDUCE_MAX && reducer != APBV_REDUCE_SOFTMAX_SUM) return APBV_ERR_SHAPE;
+  if (reducer == APBV_REDUCE_SOFTMAX_SUM && (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale))) return APBV_ERR_SHAPE;
+  const size_t need = reduced_workspace_bytes(reducer, batch, n_q_heads, n_kv_heads, head_dim, q_probe.tokens, L, l_p);
+  if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) return APBV_ERR_WORKSPACE;
+
+  CompressParams p;
+  p.q_probe = to_view(q_probe);
+  p.k = to_view(k_local);
+  p.v = to_view(v_local);
+  p.L = L;
+  p.l_p = l_p;
+  p.batch = batch;
+  p.hq = n_q_heads;
+  p.hkv = n_kv_heads;
+  p.group = n_q_heads / n_kv_heads;
+  p.d = head_dim;
+  p.idx_out = idx_out;
+  p.k_c = static_cast<bf16_t*>(k_c_out);
+  p.v_c = static_cast<bf16_t*>(v_c_out);
+  p.scores_out = scores_out;
+  p.workspace = workspace;
+  p.workspace_bytes = workspace_bytes;
+  p.reducer = reducer;
+  p.scale_log2 = softmax_scale * 1.4426950408889634f;
+  return launch_compress(p, static_cast<hipStream_t>(hip_stream));
+}
+
+
 }  // namespace
 
 extern "C" {
@@ -133,40 +184,25 @@ apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_
                              apbv_tensor k_local, apbv_tensor v_local, int64_t l_p, int32_t* idx_out, void* k_c_out,
                              void* v_c_out, double* scores_out, void* workspace, size_t workspace_bytes,
                              void* hip_stream) {
-  apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
-  if (st != APBV_OK) return st;
-  if ((st = check_view(q_probe, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if (v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
-  const int64_t L = k_local.tokens;
-  if (l_p < 0 || l_p > L) return APBV_ERR_SHAPE;
-  if (l_p > 0) {
-    if (idx_out == nullptr || k_c_out == nullptr || v_c_out == nullptr) return APBV_ERR_NULL;
-    if (!aligned(k_c_out, 16) || !aligned(v_c_out, 16) || !aligned(idx_out, 4)) return APBV_ERR_SHAPE;
-  }
-  if (scores_out != nullptr && !aligned(scores_out, 8)) return APBV_ERR_SHAPE;
-  const size_t need = compress_workspace_bytes(batch, n_kv_heads, head_dim, L, l_p);
-  if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) return APBV_ERR_WORKSPACE;
+  return compress_entry(APBV_REDUCE_SUM, 0.0f, batch, n_q_heads, n_kv_heads, head_dim, q_probe, k_local, v_local, l_p,
+                        idx_out, k_c_out, v_c_out, scores_out, workspace, workspace_bytes, hip_stream);
+}
 
-  CompressParams p;
-  p.q_probe = to_view(q_probe);
-  p.k = to_view(k_local);
-  p.v = to_view(v_local);
-  p.L = L;
-  p.l_p = l_p;
-  p.batch = batch;
-  p.hq = n_q_heads;
-  p.hkv = n_kv_heads;
-  p.group = n_q_heads / n_kv_heads;
-  p.d = head_dim;
-  p.idx_out = idx_out;
-  p.k_c = static_cast<bf16_t*>(k_c_out);
-  p.v_c = static_cast<bf16_t*>(v_c_out);
-  p.scores_out = scores_out;
-  p.workspace = workspace;
-  p.workspace_bytes = workspace_bytes;
-  return launch_compress(p, static_cast<hipStream_t>(hip_stream));
+size_t apbv_compress_reduced_workspace_bytes(int reducer, int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                                             int64_t n_q, int64_t L, int64_t l_p) {
+  if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || (head_dim != 64 && head_dim != 128) ||
+      n_q < 1 || n_q > kMaxTokens || L < 1 || L > kMaxTokens || l_p < 0 || l_p > L)
+    return 0;
+  if (reducer != APBV_REDUCE_SUM && reducer != APBV_REDUCE_MAX && reducer != APBV_REDUCE_SOFTMAX_SUM) return 0;
+  return reduced_workspace_bytes(reducer, batch, n_q_heads, n_kv_heads, head_dim, n_q, L, l_p);
+}
+
+apbv_status apbv_compress_kv_reduced(int reducer, float softmax_scale, int batch, int n_q_heads, int n_kv_heads,
+                                     int head_dim, apbv_tensor q_probe, apbv_tensor k_local, apbv_tensor v_local,
+                                     int64_t l_p, int32_t* idx_out, void* k_c_out, void* v_c_out, double* scores_out,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return compress_entry(reducer, softmax_scale, batch, n_q_heads, n_kv_heads, head_dim, q_probe, k_local, v_local, l_p,
+                        idx_out, k_c_out, v_c_out, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 apbv_status apbv_host_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_local,

@@ -549,18 +549,23 @@ apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
   double* qbar = reinterpret_cast<double*>(ws + w.qbar_off);
   double* scores = reinterpret_cast<double*>(ws + w.scores_off);
 
-  // pooled query
-  {
+  if (p.reducer != APBV_REDUCE_SUM) {
+    // the non-linear reductions form the logit matrix on the matrix cores (score_matrix.hip); their row
+    // statistics live behind the selection workspace
+    const size_t stats_off = align_up(w.total, 256);
+    const size_t stats_bytes = matrix_scores_workspace_bytes(p.reducer, p.batch, p.hkv, p.q_probe.tokens * p.group, p.L);
+    if (p.workspace_bytes < stats_off + stats_bytes) return APBV_ERR_WORKSPACE;
+    const apbv_status st = launch_matrix_scores(p, scores, ws + stats_off, stream);
+    if (st != APBV_OK) return st;
+  } else {
+    // pooled query
     if (p.d == 128)
       hipLaunchKernelGGL(pool_query_kernel<128>, dim3(p.hkv, p.batch), dim3(1024), 0, stream, p.q_probe, p.q_probe.tokens,
                          p.group, qbar, p.hkv);
     else
       hipLaunchKernelGGL(pool_query_kernel<64>, dim3(p.hkv, p.batch), dim3(1024), 0, stream, p.q_probe, p.q_probe.tokens,
                          p.group, qbar, p.hkv);
-  }
-  // scores
-  {
-    // one outer iteration per workgroup: 4 rows in flight per thread, many small workgroups
+    // scores: one outer iteration per workgroup: 4 rows in flight per thread, many small workgroups
     const int rows_per_block = 4 * 256 / (p.d / 8);
     dim3 grid((unsigned)((p.L + rows_per_block - 1) / rows_per_block), p.hkv, p.batch);
     if (p.d == 128)

@@ -1,0 +1,320 @@
+// Alternative reductions of the score matrix S_h = Q_qr K^(h)T of Alg. 1 ("Identify Essential KVs") to one
+// score per key and KV head, for gfx950.  The adopted reading (sum of the raw logits) is linear and lives in
+// compress.hip as a streaming dot product; the reductions here are not linear, so the n_q*G x L logits are
+// formed on the matrix cores (bf16 operands, fp32 accumulation) and reduced on the fly, never stored:
+//
+//   max           s[v, j] = max over rows (t, g) of S[(t, g), j]
+//   softmax-sum   s[v, j] = sum over rows of softmax_j(scale * S[(t, g), :])[j]        (Eq. 1 without a mask)
+//
+// Rows (t, g) of KV head v are Q_qr[t, v*G+g, :], r = t*G + g, R = n_q*G of them.
+//
+// One kernel template does all the matrix work.  A workgroup of four waves keeps 256 "resident" vectors in
+// registers as MFMA B operands (64 per wave) and streams the other side through LDS in tiles of 32 vectors
+// (A operand, double buffered, shared by the four waves).  Each 32x32 accumulator then has the streamed
+// vectors along its register axis and one resident vector per lane, so every reduction over the streamed side
+// is per lane, plus one exchange between the two lane halves at the end:
+//
+//   kMax     resident = keys,       streamed = all probe rows:  maximum logit               -> score per key
+//   kStats   resident = probe rows, streamed = a chunk of keys: running maximum and sum of exponentials of the
+//                                                               scaled logits               -> partial row statistics
+//   kMass    resident = keys,       streamed = all probe rows:  sum of exp2(scaled logit - c_r), c_r = the row's
+//                                   maximum + log2 of its normaliser (from kStats, merged by
+//                                   row_stats_combine_kernel)                                -> score per key
+#include "apbv_common.h"
+
+namespace apbv {
+namespace {
+
+constexpr int kChunkKeys = 256;        // keys per partial row statistic
+constexpr int kMaxStatRows = 8192;     // rows whose statistics fit the LDS of the kMass pass (4 bytes each)
+constexpr int kResident = 256;         // resident vectors per workgroup (64 per wave)
+
+enum Mode { kMax = 1, kMass = 2, kStats = 3 };
+
+__device__ __forceinline__ f32x16 mfma(const bf16x8 a, const bf16x8 b, const f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// accumulator register i of lane half hh holds matrix row 8*(i/4) + 4*hh + i%4 (column = lane % 32)
+__device__ __forceinline__ int acc_row(int i, int hh) { return 8 * (i / 4) + 4 * hh + i % 4; }
+
+// value of the lane 32 away
+__device__ __forceinline__ float other_half(float x) {
+  auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  // the swap exchanges the upper half of the first operand with the lower half of the second: each lane finds
+  // its own value in one result and its partner's in the other
+  const float a = __uint_as_float(sw[0]), b = __uint_as_float(sw[1]);
+  return (threadIdx.x & 32) ? a : b;
+}
+
+struct RowsParams {
+  View q, k;
+  int64_t L;
+  int n_rows;          // R = n_q * G
+  int r_pad;           // R rounded up to a multiple of 32
+  int group, hkv, n_chunks;
+  float scale_log2;    // softmax_scale * log2(e)
+  float2* partial;     // [batch, Hkv, n_chunks, r_pad]  (maximum of the scaled logits in the log2 domain, sum of exp2)
+  float* stats;        // [batch, Hkv, r_pad]            c_r = maximum + log2(normaliser); +inf for padding rows
+  double* s_ws;        // [batch, Hkv, L]
+  double* s_out;       // optional, same layout
+};
+
+// First element of probe row r (clamped to the last row) / of key j (clamped to the last key) of head v.
+__device__ __forceinline__ const bf16_t* probe_row(const RowsParams& p, int b, int v, int r) {
+  const int rc = r < p.n_rows ? r : p.n_rows - 1;
+  const int t = rc / p.group, g = rc % p.group;
+  return p.q.ptr + (int64_t)b * p.q.sb + (int64_t)t * p.q.st + (int64_t)(v * p.group + g) * p.q.sh;
+}
+__device__ __forceinline__ const bf16_t* key_row(const RowsParams& p, int b, int v, int64_t j) {
+  const int64_t jc = j < p.L ? j : p.L - 1;
+  return p.k.ptr + (int64_t)b * p.k.sb + (int64_t)v * p.k.sh + jc * p.k.st;
+}
+
+// Grid: kMax / kMass (ceil(L / 256), Hkv, batch); kStats (ceil(r_pad / 256) * n_chunks, Hkv, batch).
+template <int D, int MODE>
+__global__ __launch_bounds__(256) void matrix_reduce_kernel(const RowsParams p) {
+  constexpr int KS = D / 16;                 // MFMA steps along the head dimension
+  constexpr int KC = D / 8;                  // 16-byte chunks per vector
+  constexpr int ROW_BYTES = D * 2;
+  constexpr int PASSES = 32 * KC / 256;      // 16-byte loads per thread per streamed tile
+  constexpr bool kKeysResident = MODE != kStats;
+  __shared__ __attribute__((aligned(16))) unsigned char tile[2][32 * ROW_BYTES];
+  extern __shared__ float c_lds[];           // kMass: r_pad entries
+
+  const int v = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int c = lane & 31, hh = lane >> 5;
+  // swizzle of the 16-byte chunks of a tile row, so that the lanes of one A-operand read spread over the banks
+  auto swz = [](int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); };
+
+  int64_t res0;            // first resident vector of the workgroup
+  int64_t str0, str_end;   // streamed range
+  int ch = 0;
+  if (kKeysResident) {
+    res0 = (int64_t)blockIdx.x * kResident;
+    str0 = 0;
+    str_end = p.n_rows;
+  } else {
+    const int n_rg = (p.r_pad + kResident - 1) / kResident;
+    res0 = (int64_t)(blockIdx.x % n_rg) * kResident;
+    ch = blockIdx.x / n_rg;
+    str0 = (int64_t)ch * kChunkKeys;
+    str_end = str0 + kChunkKeys < p.L ? str0 + kChunkKeys : p.L;
+  }
+  auto resident_row = [&](int64_t i) { return kKeysResident ? key_row(p, b, v, i) : probe_row(p, b, v, (int)i); };
+  auto streamed_row = [&](int64_t i) { return kKeysResident ? probe_row(p, b, v, (int)i) : key_row(p, b, v, i); };
+
+  // ---- resident B operands: lane (c, hh) holds elements 8*hh + 16*kk .. +7 of vectors res + c and res + 32 + c
+  const int64_t res = res0 + wave * 64;
+  bf16x8 rf[2][KS];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const bf16_t* row = resident_row(res + 32 * s + c) + 8 * hh;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) rf[s][kk] = *reinterpret_cast<const bf16x8*>(row + 16 * kk);
+  }
+  if (MODE == kMass) {
+    const float* st = p.stats + ((int64_t)b * p.hkv + v) * p.r_pad;
+    for (int i = tid; i < p.r_pad; i += 256) c_lds[i] = st[i];
+  }
+
+  // ---- streamed tiles: thread tid moves chunk tid % KC of tile rows (u*256 + tid) / KC
+  u32x4 pre[PASSES];
+  auto fetch = [&](int64_t first) {
+#pragma unroll
+    for (int u = 0; u < PASSES; ++u) {
+      const int row = (u * 256 + tid) / KC;
+      pre[u] = *reinterpret_cast<const u32x4*>(streamed_row(first + row) + 8 * (tid % KC));
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int u = 0; u < PASSES; ++u) {
+      const int row = (u * 256 + tid) / KC;
+      *reinterpret_cast<u32x4*>(&tile[buf][row * ROW_BYTES + 16 * ((tid % KC) ^ swz(row))]) = pre[u];
+    }
+  };
+
+  float red[2], z_run[2];
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    red[s] = MODE == kMass ? 0.f : -INFINITY;      // kMax: maximum; kStats: running maximum (scaled); kMass: sum
+    z_run[s] = 0.f;
+  }
+
+  fetch(str0);
+  stash(0);
+  __syncthreads();
+  int buf = 0;
+  for (int64_t t0 = str0; t0 < str_end; t0 += 32, buf ^= 1) {
+    const bool more = t0 + 32 < str_end;
+    if (more) fetch(t0 + 32);
+    f32x16 acc[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[s][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&tile[buf][c * ROW_BYTES + 16 * ((2 * kk + hh) ^ swz(c))]);
+      acc[0] = mfma(a, rf[0][kk], acc[0]);
+      acc[1] = mfma(a, rf[1][kk], acc[1]);
+    }
+    // the accumulator's register axis runs over the streamed vectors t0 + acc_row(i, hh)
+    if (MODE == kMax) {
+      // streamed rows past the end repeat the last row: harmless under a maximum
+#pragma unroll
+      for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) red[s] = fmaxf(red[s], acc[s][i]);
+    } else if (MODE == kMass) {
+      // padding rows carry c_r = +inf: exp2(-inf) = 0
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const f32x4 cr = *reinterpret_cast<const f32x4*>(&c_lds[(t0 - str0) + 8 * i4 + 4 * hh]);
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            red[s] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[s][4 * i4 + e], p.scale_log2, -cr[e]));
+      }
+    } else {
+      const bool ragged = t0 + 32 > str_end;       // keys past the end of the block must not count
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        if (ragged) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i)
+            if (t0 + acc_row(i, hh) >= str_end) acc[s][i] = -INFINITY;
+        }
+        float bm = acc[s][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) bm = fmaxf(bm, acc[s][i]);
+        const float m_new = fmaxf(red[s], bm * p.scale_log2);
+        const float m_sub = m_new > -INFINITY ? m_new : 0.f;      // a lane half may hold only keys past the end
+        float z = z_run[s] * __builtin_amdgcn_exp2f(red[s] - m_sub);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) z += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[s][i], p.scale_log2, -m_sub));
+        z_run[s] = z;
+        red[s] = m_new;
+      }
+    }
+    if (more) stash(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- the two lane halves hold disjoint streamed vectors for the same resident vector
+#pragma unroll
+  for (int s = 0; s < 2; ++s) {
+    const int64_t i = res + 32 * s + c;
+    const float o = other_half(red[s]);
+    if (MODE == kStats) {
+      const float z_o = other_half(z_run[s]);
+      const float m_all = fmaxf(red[s], o);
+      const float m_sub = m_all > -INFINITY ? m_all : 0.f;
+      const float z_all = z_run[s] * __builtin_amdgcn_exp2f(red[s] - m_sub) + z_o * __builtin_amdgcn_exp2f(o - m_sub);
+      if (hh == 0 && i < p.r_pad) {
+        float2 w;
+        w.x = m_all;
+        w.y = z_all;
+        p.partial[(((int64_t)b * p.hkv + v) * p.n_chunks + ch) * p.r_pad + i] = w;
+      }
+    } else {
+      const float r = MODE == kMax ? fmaxf(red[s], o) : red[s] + o;      // both halves get the same bits
+      if (hh == 0 && i < p.L) {
+        const int64_t at = ((int64_t)b * p.hkv + v) * p.L + i;
+        p.s_ws[at] = (double)r;
+        if (p.s_out) p.s_out[at] = (double)r;
+      }
+    }
+  }
+}
+
+// One wave per (batch, head, row): merge the chunks' statistics into c_r = maximum + log2(normaliser); padding rows
+// get +inf.  Every real row has at least one key, so its normaliser is positive.
+__global__ __launch_bounds__(256) void row_stats_combine_kernel(const RowsParams p, int batch) {
+  const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (w >= (int64_t)batch * p.hkv * p.r_pad) return;
+  const int r = (int)(w % p.r_pad);
+  const int64_t bv = w / p.r_pad;
+  float cr = INFINITY;
+  if (r < p.n_rows) {
+    const float2* part = p.partial + bv * p.n_chunks * p.r_pad + r;
+    float m = -INFINITY;
+    for (int ch = lane; ch < p.n_chunks; ch += 64) m = fmaxf(m, part[(int64_t)ch * p.r_pad].x);
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) m = fmaxf(m, __shfl_xor(m, d));
+    float z = 0.f;
+    for (int ch = lane; ch < p.n_chunks; ch += 64) {
+      const float2 s = part[(int64_t)ch * p.r_pad];
+      z += s.y * __builtin_amdgcn_exp2f(s.x - m);
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) z += __shfl_xor(z, d);
+    cr = m + __builtin_amdgcn_logf(z);      // v_log_f32 is a base-2 logarithm
+  }
+  if (lane == 0) p.stats[w] = cr;
+}
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+
+size_t matrix_scores_workspace_bytes(int reducer, int batch, int hkv, int64_t n_rows, int64_t L) {
+  if (reducer != APBV_REDUCE_SOFTMAX_SUM) return 0;
+  const size_t r_pad = (size_t)((n_rows + 31) / 32 * 32);
+  const size_t n_chunks = (size_t)((L + kChunkKeys - 1) / kChunkKeys);
+  return align256((size_t)batch * hkv * n_chunks * r_pad * sizeof(float2)) + align256((size_t)batch * hkv * r_pad * sizeof(float));
+}
+
+apbv_status launch_matrix_scores(const CompressParams& cp, double* scores, void* stats_ws, hipStream_t stream) {
+  const int64_t n_rows = cp.q_probe.tokens * cp.group;
+  if (n_rows > (1 << 24)) return APBV_ERR_UNSUPPORTED;
+  RowsParams p;
+  p.q = cp.q_probe;
+  p.k = cp.k;
+  p.L = cp.L;
+  p.n_rows = (int)n_rows;
+  p.r_pad = (int)((n_rows + 31) / 32 * 32);
+  p.group = cp.group;
+  p.hkv = cp.hkv;
+  p.n_chunks = (int)((cp.L + kChunkKeys - 1) / kChunkKeys);
+  p.scale_log2 = cp.scale_log2;
+  p.partial = nullptr;
+  p.stats = nullptr;
+  p.s_ws = scores;
+  p.s_out = cp.scores_out;
+  const dim3 grid((unsigned)((cp.L + kResident - 1) / kResident), cp.hkv, cp.batch);
+  if (cp.reducer == APBV_REDUCE_MAX) {
+    if (cp.d == 128)
+      hipLaunchKernelGGL((matrix_reduce_kernel<128, kMax>), grid, dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((matrix_reduce_kernel<64, kMax>), grid, dim3(256), 0, stream, p);
+  } else if (cp.reducer == APBV_REDUCE_SOFTMAX_SUM) {
+    if (p.r_pad > kMaxStatRows) return APBV_ERR_UNSUPPORTED;
+    p.partial = static_cast<float2*>(stats_ws);
+    p.stats = reinterpret_cast<float*>(static_cast<char*>(stats_ws) +
+                                       align256((size_t)cp.batch * cp.hkv * p.n_chunks * p.r_pad * sizeof(float2)));
+    const int64_t n_wg = (int64_t)((p.r_pad + kResident - 1) / kResident) * p.n_chunks;
+    if (n_wg > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
+    const dim3 sgrid((unsigned)n_wg, cp.hkv, cp.batch);
+    if (cp.d == 128)
+      hipLaunchKernelGGL((matrix_reduce_kernel<128, kStats>), sgrid, dim3(256), 0, stream, p);
+    else
+      hipLaunchKernelGGL((matrix_reduce_kernel<64, kStats>), sgrid, dim3(256), 0, stream, p);
+    const int64_t n_stat = (int64_t)cp.batch * cp.hkv * p.r_pad;
+    hipLaunchKernelGGL(row_stats_combine_kernel, dim3((unsigned)((n_stat + 3) / 4)), dim3(256), 0, stream, p, cp.batch);
+    const size_t lds = (size_t)p.r_pad * sizeof(float);
+    if (cp.d == 128)
+      hipLaunchKernelGGL((matrix_reduce_kernel<128, kMass>), grid, dim3(256), lds, stream, p);
+    else
+      hipLaunchKernelGGL((matrix_reduce_kernel<64, kMass>), grid, dim3(256), lds, stream, p);
+  } else {
+    return APBV_ERR_UNSUPPORTED;
+  }
+  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+}
+
+}  // namespace apbv

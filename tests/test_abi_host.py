@@ -21,7 +21,8 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = apbv.load_library()
     names = declared_symbols()
-    assert names == ["apbv_compress_kv", "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_host_attention_group",
+    assert names == ["apbv_compress_kv", "apbv_compress_kv_reduced", "apbv_compress_reduced_workspace_bytes",
+                     "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_host_attention_group",
                      "apbv_merge_lse",
                      "apbv_query_attention", "apbv_query_attention_workspace_bytes", "apbv_status_string",
                      "apbv_version"]
@@ -94,6 +95,28 @@ def test_compress_rejects_bad_arguments_without_launching():
     assert call_compress(n_q=0) == -2
     assert call_compress(v=view(63, 2, 128)) == -2
     assert call_compress(kc=0x4002) == -2
+
+
+def test_compress_reduced_rejects_bad_arguments_without_launching():
+    lib = apbv.load_library()
+    ws = apbv.apbv_compress_reduced_workspace_bytes
+    base = apbv.apbv_compress_workspace_bytes(1, 2, 128, 4096, 64)
+    assert ws("sum", 1, 4, 2, 128, 8, 4096, 64) == base
+    assert ws("max", 1, 4, 2, 128, 8, 4096, 64) == (base + 255) // 256 * 256          # no row statistics
+    # softmax-sum: 16 rows -> 32 padded, 16 chunks of 256 keys, 2 heads: partial statistics of 8 bytes, final of 4
+    assert ws("softmax_sum", 1, 4, 2, 128, 8, 4096, 64) == (base + 255) // 256 * 256 + 2 * 16 * 32 * 8 + 2 * 32 * 4
+    assert lib.apbv_compress_reduced_workspace_bytes(7, 1, 4, 2, 128, 8, 4096, 64) == 0
+    assert lib.apbv_compress_reduced_workspace_bytes(1, 1, 5, 2, 128, 8, 4096, 64) == 0
+
+    def call(reducer=2, scale=0.1, n_q=8, L=4096, ws_bytes=1 << 24, hq=4):
+        return lib.apbv_compress_kv_reduced(reducer, scale, 1, hq, 2, 128, view(n_q, hq, 128), view(L, 2, 128),
+                                            view(L, 2, 128), 64, 0x3000, 0x4000, 0x5000, None, 0x10000, ws_bytes, None)
+    assert call(reducer=3) == -2 and call(reducer=-1) == -2
+    assert call(scale=0.0) == -2 and call(scale=float("inf")) == -2
+    assert call(reducer=1, scale=0.0, ws_bytes=64) == -4          # the scale is ignored by the maximum; workspace too small
+    need = ws("softmax_sum", 1, 4, 2, 128, 8, 4096, 64)
+    assert call(ws_bytes=need - 1) == -4
+    assert call(n_q=4200, ws_bytes=1 << 30) == -3                 # 8400 rows: more than the softmax-sum kernels stage
 
 
 def test_merge_rejects_bad_arguments_without_launching():
