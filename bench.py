@@ -47,6 +47,8 @@ def parse_args():
     ap.add_argument("--cpu-rows", type=int, default=6144, help="query rows the oracle is timed on")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--no-extras", action="store_true", help="skip the short timings of the query-block, physical-host "
+                    "and alternative-reduction entry points")
     ap.add_argument("--compress-batch", type=int, default=96,
                     help="batch of the HBM-bound compression measurement (working set far beyond the 256 MB cache)")
     return ap.parse_args()
@@ -172,9 +174,80 @@ def main():
         del src, dst
     if not args.no_compress_roofline:
         result["roofline_compress"] = compress_roofline(apbv, torch, cfg, q_probe, k, v, args.compress_batch)
+    if not args.no_extras:
+        result["extras"] = extras(apbv, torch, cfg, q_probe, q, k_a, v_a, k_p, v_p, k, v, scale)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(np, x, cfg, scale, args.cpu_rows)
     print(json.dumps(result), flush=True)
+
+
+def timed(torch, fn, iters=10, warmup=3):
+    """Average milliseconds per call of fn() on the current stream (HIP events)."""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def extras(apbv, torch, cfg, q_probe, q, k_a, v_a, k_p, v_p, k, v, scale):
+    """Short timings of the entry points beyond the two-call hot path, at the same workload's shapes (context, not
+    part of `value`): the query block's attention with and without the key split, a physical host's three attention
+    problems in one launch and in three, and the alternative score reductions."""
+    hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    empty = torch.empty((0, hkv, d), dtype=torch.bfloat16, device="cuda")
+    out = {}
+    # query block of n_q tokens over this host's anchor + context block (Eq. 5), no causal segment
+    n_keys = cfg.l_a + cfg.L
+    q_out = torch.empty((1, cfg.n_q, hq, d), dtype=torch.bfloat16, device="cuda")
+    nb = apbv.apbv_query_attention_workspace_bytes(1, hq, d, cfg.n_q, n_keys, 0)
+    qws = torch.empty(max(nb, 256), dtype=torch.uint8, device="cuda")
+    ms_split = timed(torch, lambda: apbv.apbv_query_attention(q_probe, k_a, v_a, k, v, empty, empty, scale, out=q_out,
+                                                              workspace=qws))
+    ms_plain = timed(torch, lambda: apbv.apbv_host_attention(q_probe, k_a, v_a, k, v, empty, empty, scale, out=q_out))
+    out["query_attention"] = {"n_q": cfg.n_q, "keys": n_keys, "us_key_split": round(ms_split * 1e3, 1),
+                              "us_unsplit": round(ms_plain * 1e3, 1)}
+    # physical host 0 of 8: anchor block, virtual host 0 (no passing keys), virtual host 15 (15 passing blocks)
+    def passing(n_blocks):
+        reps = -(-n_blocks // max(cfg.P, 1))
+        return (torch.cat([k_p] * reps)[: n_blocks * cfg.l_p].contiguous(), torch.cat([v_p] * reps)[: n_blocks * cfg.l_p].contiguous())
+    if cfg.P > 0:
+        kp15, vp15 = passing(15)
+        qa = q[: cfg.l_a].contiguous()
+        probs = [(qa, empty, empty, empty, empty, k_a, v_a),
+                 (q, k_a, v_a, empty, empty, k, v),
+                 (q, k_a, v_a, kp15, vp15, k, v)]
+        outs = [torch.empty((p[0].shape[0], hq, d), dtype=torch.bfloat16, device="cuda") for p in probs]
+        with_out = [p + (o,) for p, o in zip(probs, outs)]
+        flops = sum(4.0 * hq * d * (p[0].shape[0] * (p[1].shape[0] + p[3].shape[0]) + p[0].shape[0] * (p[0].shape[0] + 1) / 2)
+                    for p in probs)
+        ms_group = timed(torch, lambda: apbv.apbv_host_attention_group(with_out, scale))
+
+        def separate():
+            for p, o in zip(probs, outs):
+                apbv.apbv_host_attention(*p, scale, out=o)
+        ms_sep = timed(torch, separate)
+        out["physical_host"] = {"problems": "anchor 2048 causal; block with 0 passing keys; block with 15 x l_p passing keys",
+                                "ms_one_launch": round(ms_group, 4), "ms_three_launches": round(ms_sep, 4),
+                                "tflops_one_launch": round(flops / (ms_group * 1e-3) / 1e12, 1)}
+    # alternative reductions of the score matrix, whole compression call at batch 1
+    red = {}
+    for name in ("sum", "max", "softmax_sum"):
+        nbytes = apbv.apbv_compress_reduced_workspace_bytes(name, 1, hq, hkv, d, cfg.n_q, cfg.L, cfg.l_p)
+        rws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        idx = torch.empty((1, hkv, cfg.l_p), dtype=torch.int32, device="cuda")
+        k_c = torch.empty((1, cfg.l_p, hkv, d), dtype=torch.bfloat16, device="cuda")
+        v_c = torch.empty_like(k_c)
+        ms = timed(torch, lambda: apbv.apbv_compress_kv(q_probe, k, v, cfg.l_p, reducer=name, softmax_scale=scale,
+                                                        workspace=rws, idx_out=idx, k_c_out=k_c, v_c_out=v_c), iters=20)
+        red[name] = round(ms * 1e3, 1)
+    out["compress_us_by_reducer"] = red
+    return out
 
 
 def compress_roofline(apbv, torch, cfg, q_probe, k, v, batch):
@@ -208,9 +281,26 @@ def compress_roofline(apbv, torch, cfg, q_probe, k, v, batch):
     ms = e0.elapsed_time(e1) / iters
     nbytes = cfg.compress_bytes * batch
     gbps = nbytes / (ms * 1e-3) / 1e9
+    # the streaming pass on its own (l_p = 0: pooled query + scores, nothing selected or gathered); its
+    # algorithmic bytes are the K block read once
+    for i in range(2):
+        apbv.apbv_compress_kv(qp, sets[i % 2][0], sets[i % 2][1], 0, workspace=ws)
+    torch.cuda.synchronize()
+    e0.record()
+    for i in range(iters):
+        kb, vb = sets[i % 2]
+        apbv.apbv_compress_kv(qp, kb, vb, 0, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_score = e0.elapsed_time(e1) / iters
+    k_bytes = cfg.L * cfg.n_kv_heads * cfg.head_dim * 2 * batch
+    gbps_score = k_bytes / (ms_score * 1e-3) / 1e9
     return {"bound": "hbm", "kernel": "pool+score+select+gather", "batch": batch, "achieved": round(gbps, 1),
             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
-            "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes, "traffic": None}
+            "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes, "traffic": None,
+            "score_pass": {"kernel": "pool+score (l_p = 0)", "achieved": round(gbps_score, 1), "unit": "GB/s",
+                           "frac": round(gbps_score / PEAK_HBM_GBPS, 4), "ms_per_call": round(ms_score, 4),
+                           "algorithmic_bytes_per_call": k_bytes}}
 
 
 def cpu_baseline(np, x, cfg, scale, n_rows):

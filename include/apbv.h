@@ -85,7 +85,7 @@ size_t apbv_compress_workspace_bytes(int batch, int n_kv_heads, int head_dim, in
  *   scores_out  optional (may be NULL): [batch, Hkv, L] float64, the ranking scores s
  *   workspace / workspace_bytes   at least apbv_compress_workspace_bytes(...) bytes, 256-byte aligned
  *
- * Supported: head_dim in {64, 128}; L <= 2^24; n_q_heads % n_kv_heads == 0.
+ * Supported: head_dim in {64, 128}; L <= 2^24; n_q_heads % n_kv_heads == 0; n_q * G <= 2^24.
  */
 apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_dim,
                              apbv_tensor q_probe, apbv_tensor k_local, apbv_tensor v_local,

@@ -129,6 +129,7 @@ apbv_status compress_entry(int reducer, float softmax_scale, int batch, int n_q_
   }
   if (scores_out != nullptr && !aligned(scores_out, 8)) return APBV_ERR_SHAPE;
   if (reducer != APBV_REDUCE_SUM && reducer != APBV_REDUCE_MAX && reducer != APBV_REDUCE_SOFTMAX_SUM) return APBV_ERR_SHAPE;
+  if (q_probe.tokens * (n_q_heads / n_kv_heads) > (int64_t)1 << 24) return APBV_ERR_UNSUPPORTED;   // rows of the score matrix per KV head
   if (reducer == APBV_REDUCE_SOFTMAX_SUM && (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale))) return APBV_ERR_SHAPE;
   const size_t need = reduced_workspace_bytes(reducer, batch, n_q_heads, n_kv_heads, head_dim, q_probe.tokens, L, l_p);
   if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) return APBV_ERR_WORKSPACE;

@@ -93,15 +93,33 @@ __global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, i
   double acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.0;
-  const int64_t n_rows = n_q * group;
-  for (int64_t rr = rg; rr < n_rows; rr += R) {
-    const int64_t t = rr / group, g = rr % group;
-    const u32x4 x = *reinterpret_cast<const u32x4*>(base + t * q.st + g * q.sh);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      acc[2 * e] += bf16_to_f64(x[e] & 0xffffu);
-      acc[2 * e + 1] += bf16_to_f64(x[e] >> 16);
+  // rows (t, g) in steps of R, four loads in flight; (t, g) advance without divisions in the loop
+  const int n_rows = (int)(n_q * group);
+  const int dt = R / group, dg = R % group;
+  int t = rg / group, g = rg % group;
+  auto advance = [&]() {
+    t += dt;
+    g += dg;
+    if (g >= group) {
+      g -= group;
+      ++t;
     }
+  };
+  for (int rr = rg; rr < n_rows; rr += 4 * R) {
+    u32x4 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      x[u] = u32x4{0u, 0u, 0u, 0u};                       // +0.0: adds nothing
+      if (rr + u * R < n_rows) x[u] = *reinterpret_cast<const u32x4*>(base + (int64_t)t * q.st + (int64_t)g * q.sh);
+      advance();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[2 * e] += bf16_to_f64(x[u][e] & 0xffffu);
+        acc[2 * e + 1] += bf16_to_f64(x[u][e] >> 16);
+      }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
