@@ -59,3 +59,58 @@ def test_layer_step_replays_bit_identically_from_a_hip_graph():
         torch.cuda.synchronize()
         assert torch.equal(out, ref_out), f"replay {rep}: attention output differs"
         assert torch.equal(idx, ref_idx) and torch.equal(kp, ref_kp), f"replay {rep}: compression differs"
+
+
+def test_query_group_and_reduced_entry_points_replay_from_a_hip_graph():
+    """The multi-kernel entry points (key-split attention + merge, grouped attention, the matrix reductions with
+    their row statistics) captured in one graph: replays equal the eager results bit for bit."""
+    rng = np.random.default_rng(61)
+    hq, hkv, d, n_q, l_a, L, lp = 8, 2, 128, 40, 96, 1500, 64
+    scale = 1.0 / math.sqrt(d)
+
+    def rnd(*shape):
+        return dev(wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32)))
+
+    q_probe, q, k_a, v_a, k, v = rnd(n_q, hq, d), rnd(L, hq, d), rnd(l_a, hkv, d), rnd(l_a, hkv, d), rnd(L, hkv, d), rnd(L, hkv, d)
+    e = torch.empty((0, hkv, d), dtype=torch.bfloat16, device="cuda")
+    q_out = torch.empty((1, n_q, hq, d), dtype=torch.bfloat16, device="cuda")
+    q_ws = torch.empty(max(apbv.apbv_query_attention_workspace_bytes(1, hq, d, n_q, l_a + L, 5), 256), dtype=torch.uint8, device="cuda")
+    g_out = [torch.empty((l_a, hq, d), dtype=torch.bfloat16, device="cuda"), torch.empty((L, hq, d), dtype=torch.bfloat16, device="cuda")]
+    probs = [(q[:l_a].contiguous(), e, e, e, e, k_a, v_a, g_out[0]), (q, k_a, v_a, e, e, k, v, g_out[1])]
+    r_ws = torch.empty(apbv.apbv_compress_reduced_workspace_bytes("softmax_sum", 1, hq, hkv, d, n_q, L, lp), dtype=torch.uint8, device="cuda")
+    idx = torch.empty((2, 1, hkv, lp), dtype=torch.int32, device="cuda")
+    k_c = torch.empty((2, 1, lp, hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_c = torch.empty_like(k_c)
+
+    def step():
+        apbv.apbv_query_attention(q_probe, k_a, v_a, k, v, e, e, scale, n_splits=5, out=q_out, workspace=q_ws)
+        apbv.apbv_host_attention_group(probs, scale)
+        for i, red in enumerate(("max", "softmax_sum")):
+            apbv.apbv_compress_kv(q_probe, k, v, lp, reducer=red, softmax_scale=scale, workspace=r_ws, idx_out=idx[i],
+                                  k_c_out=k_c[i], v_c_out=v_c[i])
+
+    results = (q_out, g_out[0], g_out[1], idx, k_c, v_c)
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in results]
+
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in results:
+            t.fill_(0)
+        q_ws.fill_(0)
+        r_ws.fill_(0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for name, t, r in zip(("query", "anchor", "block", "idx", "k_c", "v_c"), results, ref):
+            assert torch.equal(t.view(torch.int16) if t.dtype == torch.bfloat16 else t,
+                               r.view(torch.int16) if r.dtype == torch.bfloat16 else r), f"replay {rep}: {name} differs"
