@@ -34,6 +34,8 @@ PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E, published
 # each scaled by the same counter's reading for a copy kernel of known size; see profiles/.  None until
 # measured.
 MEASURED_TRAFFIC_BYTES = 446905394   # profiles/host_attention_3b-128k_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB)
+# the same for one batch-96 compression call (its four kernels together); profiles/compress_3b-128k_batch96_pmc.txt
+MEASURED_COMPRESS_TRAFFIC_BYTES = 1088141755
 
 
 def parse_args():
@@ -163,6 +165,17 @@ def main():
                      "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_MFMA_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES},
     }
+
+    # the two virtual hosts of a physical host as one batched call (Sec. 4.3)
+    k2, v2, qp2 = (t.unsqueeze(0).repeat(2, 1, 1, 1) for t in (k, v, q_probe))
+    ws2 = torch.empty(apbv.apbv_compress_workspace_bytes(2, cfg.n_kv_heads, cfg.head_dim, cfg.L, cfg.l_p), dtype=torch.uint8, device="cuda")
+    idx2 = torch.empty((2, cfg.n_kv_heads, cfg.l_p), dtype=torch.int32, device="cuda")
+    kc2 = torch.empty((2, cfg.l_p, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+    vc2 = torch.empty_like(kc2)
+    ms2 = timed(torch, lambda: apbv.apbv_compress_kv(qp2, k2, v2, cfg.l_p, workspace=ws2, idx_out=idx2, k_c_out=kc2, v_c_out=vc2),
+                iters=20)
+    result["compress_batch2"] = {"us_avg": round(ms2 * 1e3, 2), "gbps": round(2 * cfg.compress_bytes / (ms2 * 1e-3) / 1e9, 2)}
+    del k2, v2, qp2
 
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
@@ -297,7 +310,8 @@ def compress_roofline(apbv, torch, cfg, q_probe, k, v, batch):
     gbps_score = k_bytes / (ms_score * 1e-3) / 1e9
     return {"bound": "hbm", "kernel": "pool+score+select+gather", "batch": batch, "achieved": round(gbps, 1),
             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
-            "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes, "traffic": None,
+            "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes,
+            "traffic": MEASURED_COMPRESS_TRAFFIC_BYTES if batch == 96 else None,
             "score_pass": {"kernel": "pool+score (l_p = 0)", "achieved": round(gbps_score, 1), "unit": "GB/s",
                            "frac": round(gbps_score / PEAK_HBM_GBPS, 4), "ms_per_call": round(ms_score, 4),
                            "algorithmic_bytes_per_call": k_bytes}}
