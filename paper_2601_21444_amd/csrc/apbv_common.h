@@ -55,6 +55,8 @@ struct AttnParams {
 };
 constexpr int kAttnKeyTile = 64;      // keys per tile of the attention kernel
 constexpr int kAttnQueryTile = 256;   // query rows per workgroup
+constexpr int kAttnNarrowQueryTile = 64;    // ... of the variant used for query blocks of at most
+constexpr int kAttnNarrowMaxRows = 128;     // this many rows
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream);
 

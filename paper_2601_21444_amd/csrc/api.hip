@@ -89,7 +89,8 @@ KeySplit plan_key_split(int batch, int n_q_heads, int64_t n_q, int64_t n_keys, i
   const int64_t n_tiles = (n_keys + kAttnKeyTile - 1) / kAttnKeyTile;
   int64_t s = requested;
   if (s <= 0) {
-    const int64_t wgs = (n_q + kAttnQueryTile - 1) / kAttnQueryTile * n_q_heads * batch;
+    const int64_t tile = n_q <= kAttnNarrowMaxRows ? kAttnNarrowQueryTile : kAttnQueryTile;
+    const int64_t wgs = (n_q + tile - 1) / tile * n_q_heads * batch;
     s = (512 + wgs - 1) / wgs;
     const int64_t cap = n_tiles / 4 > 1 ? n_tiles / 4 : 1;
     s = s < cap ? s : cap;

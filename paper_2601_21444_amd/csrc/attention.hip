@@ -45,9 +45,9 @@
 namespace apbv {
 namespace {
 
-constexpr int kWaves = 8;
-constexpr int kThreads = kWaves * 64;
-constexpr int kBM = 32 * kWaves;   // query rows per workgroup
+constexpr int kWaves = 8;          // waves per workgroup of the main variant: 256 query rows
+constexpr int kWavesNarrow = 2;    // of the variant for short query blocks: 64 query rows
+constexpr int kBM = 32 * kWaves;   // query rows per workgroup (main variant)
 constexpr int kBN = 64;            // keys per tile
 constexpr int kXcds = 8;
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
@@ -57,12 +57,12 @@ constexpr float kRescaleThreshold = 8.0f;   // log2 units
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-template <int D>
+template <int D, int W>
 struct Tile {
   static constexpr int ROW_BYTES = D * 2;
   static constexpr int KC = D / 8;                        // 16-byte chunks per row
   static constexpr int RPI = 1024 / ROW_BYTES;            // rows covered by one wave-wide LDS-direct load
-  static constexpr int IPW = kBN / RPI / kWaves;          // such loads per wave per tile (per tensor)
+  static constexpr int IPW = kBN / RPI / W;              // such loads per wave per tile (per tensor)
   static constexpr int KS = D / 16;                       // MFMA k-steps over the head dimension
   static constexpr int DB = D / 32;                       // 32-row blocks of O^T
   static constexpr int TILE_BYTES = kBN * ROW_BYTES;
@@ -90,6 +90,11 @@ __device__ __forceinline__ void seg_of(const Segs sg, int64_t j, const char*& ba
 // LDS-direct 16-byte load: lane l's bytes land at lds_dst + 16*l (lds_dst uniform, in M0).  Issued through
 // inline assembly so that the kernel, not the compiler's wait-count insertion, orders these loads against
 // the LDS reads (one s_waitcnt vmcnt + barrier per tile).
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {      // a wave-uniform pointer, provably so
+  const uint64_t v = (uint64_t)p;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+  return (const char*)(((uint64_t)hi << 32) | lo);
+}
 __device__ __forceinline__ void dma16_uniform(const char* base_uniform, uint32_t lane_off, uint32_t lds_dst) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(lane_off), "s"(base_uniform)
                : "memory");
@@ -103,9 +108,9 @@ __device__ __forceinline__ uint32_t lds_addr(const unsigned char* p) { return (u
 // one segment ("run") a tile costs two 64-bit scalar adds and its loads are  uniform tile base + a per-lane
 // 32-bit offset computed once per run; the tile that straddles a segment boundary (or the end of the keys)
 // takes a per-row lookup.
-template <int D>
+template <int D, int W>
 struct TileStream {
-  using T = Tile<D>;
+  using T = Tile<D, W>;
   Segs ks, vs;             // e0/e1/e2 are shared
   int64_t s_kv;
   int t_next;              // next tile to issue
@@ -157,10 +162,12 @@ struct TileStream {
   __device__ __forceinline__ void issue(uint32_t k_dst, uint32_t v_dst) {
     if (t_next >= run_end) start_run();
     if (t_next < run_end) {
+      const char* kbu = uniform_ptr(kb);
+      const char* vbu = uniform_ptr(vb);
 #pragma unroll
-      for (int u = 0; u < T::IPW; ++u) dma16_uniform(kb, koff[u], k_dst + ldst(u));
+      for (int u = 0; u < T::IPW; ++u) dma16_uniform(kbu, koff[u], k_dst + ldst(u));
 #pragma unroll
-      for (int u = 0; u < T::IPW; ++u) dma16_uniform(vb, voff[u], v_dst + ldst(u));
+      for (int u = 0; u < T::IPW; ++u) dma16_uniform(vbu, voff[u], v_dst + ldst(u));
       kb += kstep;
       vb += vstep;
     } else {
@@ -183,10 +190,11 @@ struct TileStream {
 };
 
 // One workgroup's work: query tile `qt` of query head (kvh, g) of batch item b, key range `split`.
-template <int D>
+template <int D, int W>
 __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const int qt, const int b, const int kvh,
                                                     const int g, const int split) {
-  using T = Tile<D>;
+  using T = Tile<D, W>;
+  constexpr int kRows = 32 * W;      // query rows of the workgroup
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds0[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[T::TILE_BYTES];
@@ -199,7 +207,7 @@ __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const i
   const int lq = lane & 31;       // query column / A-operand row within a 32-block
   const int hh = lane >> 5;       // lane half
 
-  const int64_t i0 = (int64_t)qt * kBM;                 // first query position of the workgroup
+  const int64_t i0 = (int64_t)qt * kRows;               // first query position of the workgroup
   const int64_t iw = i0 + wave * 32;                    // first query position of the wave
   const int64_t i_row = iw + lq;                        // this lane's query position
 
@@ -257,7 +265,7 @@ __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const i
   // Query i sees the virtual keys 0 .. min(i + n_vis, s_kv - 1); the second bound only matters when there is no
   // causal segment (s_kv == n_vis: every key visible to every query).
   auto last_key = [&](int64_t i) { return (i + p.n_vis < p.s_kv - 1) ? i + p.n_vis : p.s_kv - 1; };
-  const int64_t i_last_wg = (i0 + kBM - 1 < p.L - 1) ? i0 + kBM - 1 : p.L - 1;
+  const int64_t i_last_wg = (i0 + kRows - 1 < p.L - 1) ? i0 + kRows - 1 : p.L - 1;
   const int n_tiles_vis = (int)(last_key(i_last_wg) / kBN) + 1;      // tiles the workgroup can see into
   // key split (partial results merged afterwards): this workgroup walks tiles [t_begin, n_tiles) only
   const int t_begin = split * p.tiles_per_split;
@@ -370,7 +378,7 @@ __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const i
   };
 
   // ---- key loop: LDS double buffer, the loads of tile t+1 in flight while tile t is computed
-  TileStream<D> ts;
+  TileStream<D, W> ts;
   ts.init(ks, vs, p.s_kv, wave, lane, t_begin);
   const uint32_t k0 = lds_addr(k_lds0), k1 = lds_addr(k_lds1), v0 = lds_addr(v_lds0), v1 = lds_addr(v_lds1);
   // The Q fragments are in (vmcnt 0, other counters untouched): from here on only tile loads are
@@ -418,9 +426,9 @@ __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const i
 }
 
 // ---- workgroup -> (query tile, head, batch, key range); the heads of one KV group share an XCD
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles,
-                                                                     const int n_items) {
+template <int D, int W>
+__global__ __launch_bounds__(64 * W, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles,
+                                                                   const int n_items) {
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
   const int item_split = (slot / p.group) * kXcds + xcd;
@@ -432,14 +440,14 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_kernel(const AttnP
   const int qt = n_qtiles - 1 - item / bh;       // heaviest query tiles first
   const int b = (item % bh) / p.hkv;
   const int kvh = (item % bh) % p.hkv;
-  attention_workgroup<D>(p, qt, b, kvh, g, split);
+  attention_workgroup<D, W>(p, qt, b, kvh, g, split);
 }
 
 // ---- several attention problems of different lengths in one launch (the two virtual hosts and the anchor
 // block of a physical host, Alg. 1 / Sec. 4.3): one workgroup per entry of the merged heaviest-first order of
 // all (problem, query tile) pairs, per KV head and group member.
 template <int D>
-__global__ __launch_bounds__(kThreads, 2) void host_attention_group_kernel(const AttnGroupParams gp) {
+__global__ __launch_bounds__(64 * kWaves, 2) void host_attention_group_kernel(const AttnGroupParams gp) {
   const int group = gp.item[0].group, hkv = gp.item[0].hkv;
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
@@ -450,25 +458,35 @@ __global__ __launch_bounds__(kThreads, 2) void host_attention_group_kernel(const
   int m, qt;
   decode_group_entry(gp.sched, entry, m, qt);
   if (m >= gp.n_items || qt < 0 || (int64_t)qt * kBM >= gp.item[m].L) return;      // never taken for a schedule the launcher built
-  attention_workgroup<D>(gp.item[m], qt, 0, kvh, g, 0);
+  attention_workgroup<D, kWaves>(gp.item[m], qt, 0, kvh, g, 0);
 }
 
 }  // namespace
 
-apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream) {
-  const int n_qtiles = (int)((p.L + kBM - 1) / kBM);
+template <int W>
+static apbv_status launch_variant(const AttnParams& p, int head_dim, hipStream_t stream) {
+  constexpr int kRows = 32 * W;
+  const int n_qtiles = (int)((p.L + kRows - 1) / kRows);
   const int64_t n_items = (int64_t)n_qtiles * p.batch * p.hkv * p.n_splits;
   const int64_t n_blocks = (n_items + kXcds - 1) / kXcds * kXcds * p.group;
   if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_blocks);
-  dim3 block(kThreads);
+  dim3 block(64 * W);
   if (head_dim == 128)
-    hipLaunchKernelGGL(host_attention_kernel<128>, grid, block, 0, stream, p, n_qtiles, (int)n_items);
+    hipLaunchKernelGGL((host_attention_kernel<128, W>), grid, block, 0, stream, p, n_qtiles, (int)n_items);
   else if (head_dim == 64)
-    hipLaunchKernelGGL(host_attention_kernel<64>, grid, block, 0, stream, p, n_qtiles, (int)n_items);
+    hipLaunchKernelGGL((host_attention_kernel<64, W>), grid, block, 0, stream, p, n_qtiles, (int)n_items);
   else
     return APBV_ERR_UNSUPPORTED;
   return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+}
+
+// Query blocks of at most kAttnNarrowMaxRows rows take the 64-row workgroups: a 256-row tile would compute mostly
+// padding rows for them.
+apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream) {
+  static_assert(kAttnQueryTile == kBM && kAttnNarrowQueryTile == 32 * kWavesNarrow, "tile sizes the host-side planning assumes");
+  if (p.L <= kAttnNarrowMaxRows) return launch_variant<kWavesNarrow>(p, head_dim, stream);
+  return launch_variant<kWaves>(p, head_dim, stream);
 }
 
 apbv_status launch_host_attention_group(AttnGroupParams& gp, int head_dim, hipStream_t stream) {
@@ -488,7 +506,7 @@ apbv_status launch_host_attention_group(AttnGroupParams& gp, int head_dim, hipSt
   const int64_t n_blocks = (n_units + kXcds - 1) / kXcds * kXcds * p0.group;
   if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_blocks);
-  dim3 block(kThreads);
+  dim3 block(64 * kWaves);
   if (head_dim == 128)
     hipLaunchKernelGGL(host_attention_group_kernel<128>, grid, block, 0, stream, gp);
   else if (head_dim == 64)
