@@ -1,0 +1,79 @@
+"""Seeded random-shape sweep of every attention entry point against the fp64 oracle: ragged lengths around the
+tile sizes (64-key tiles, 64- and 256-row workgroups), empty segments, both head dimensions, strided views."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2601_21444_amd as apbv
+from paper_2601_21444_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(bits):
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+
+
+def to_f64(t):
+    return wl.bf16_bits_to_f32(t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+
+
+def rand_bits(rng, shape):
+    return wl.f32_to_bf16_bits(rng.standard_normal(shape).astype(np.float32))
+
+
+def pick_len(rng, choices=(0, 1, 31, 63, 64, 65, 127, 128, 129, 255, 256, 257, 300, 511, 640)):
+    return int(rng.choice(choices))
+
+
+def check(out_gpu, ref, what):
+    diff = np.abs(out_gpu - ref)
+    assert np.all(np.isfinite(out_gpu)), what
+    assert diff.max() <= 2e-2 and diff.mean() / np.abs(ref).mean() <= 5e-3, \
+        f"{what}: max_abs={diff.max():.3e} mean_rel={diff.mean() / np.abs(ref).mean():.3e}"
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes_all_attention_entry_points(seed):
+    rng = np.random.default_rng((71, seed))
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 3]))
+    hq = hkv * int(rng.choice([1, 2, 4, 7]))
+    scale = 1.0 / math.sqrt(d)
+    L = max(pick_len(rng), 1)
+    l_a, n_p = pick_len(rng), pick_len(rng)
+    causal = bool(rng.integers(0, 2)) or (l_a + n_p == 0)
+    n_l = L if causal else 0
+    q = rand_bits(rng, (L, hq, d))
+    ka, va, kp, vp, kl, vl = (rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_p, n_p, n_l, n_l))
+    print(f"random shape seed={seed}: hq={hq} hkv={hkv} d={d} L={L} l_a={l_a} n_p={n_p} causal={causal}", flush=True)
+    ref, lse_r = oracle.host_attention(q, ka, va, kp, vp, kl, vl, scale)
+    # passing keys as a strided view (rows padded), everything else dense
+    kp_wide = torch.zeros((n_p, hkv, d + 8), dtype=torch.bfloat16, device="cuda")
+    kp_wide[..., :d] = dev(kp)
+    args = [dev(q), dev(ka), dev(va), kp_wide[..., :d], dev(vp), dev(kl), dev(vl)]
+
+    out, lse = apbv.apbv_host_attention(*args, scale, return_lse=True)
+    torch.cuda.synchronize()
+    check(to_f64(out), ref, "host_attention")
+    np.testing.assert_allclose(lse.cpu().numpy().astype(np.float64), lse_r, atol=2e-3, rtol=0)
+
+    n_splits = int(rng.choice([0, 2, 3, 7]))
+    out_s, lse_s = apbv.apbv_query_attention(*args, scale, n_splits=n_splits, return_lse=True)
+    torch.cuda.synchronize()
+    check(to_f64(out_s), ref, f"query_attention n_splits={n_splits}")
+    np.testing.assert_allclose(lse_s.cpu().numpy().astype(np.float64), lse_r, atol=2e-3, rtol=0)
+
+    if causal:
+        # the same problem twice in a group with a second, different one in between
+        L2 = max(pick_len(rng), 1)
+        other = [rand_bits(rng, (L2, hq, d))] + [rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, 0, 0, L2, L2)]
+        res = apbv.apbv_host_attention_group([tuple(args), tuple(dev(x) for x in other), tuple(args)], scale)
+        torch.cuda.synchronize()
+        assert torch.equal(res[0].view(torch.int16), out.view(torch.int16))
+        assert torch.equal(res[2].view(torch.int16), out.view(torch.int16))
+        ref2, _ = oracle.host_attention(*other, scale)
+        check(to_f64(res[1]), ref2, "group, second problem")
