@@ -71,15 +71,67 @@ __device__ __forceinline__ const bf16_t* key_row(const RowsParams& p, int b, int
   return p.k.ptr + (int64_t)b * p.k.sb + (int64_t)v * p.k.sh + jc * p.k.st;
 }
 
+// A cursor keeps one row's address and advances it without divisions
+// (the streamed loads would otherwise cost more vector instructions than the reduction itself).  Rows past
+// the end read the last row.
+struct ProbeCursor {
+  const bf16_t *ptr, *last;
+  int r, g, dr;
+  int64_t step, wrap;      // elements per step of dr rows without / extra on a carry of g
+  int dg;
+  __device__ __forceinline__ void init(const RowsParams& p, int b, int v, int r0, int chunk_elems, int rows_per_step) {
+    r = r0;
+    dr = rows_per_step;
+    last = probe_row(p, b, v, p.n_rows - 1) + chunk_elems;
+    ptr = probe_row(p, b, v, r0) + chunk_elems;
+    g = (r0 < p.n_rows ? r0 : p.n_rows - 1) % p.group;
+    dg = rows_per_step % p.group;
+    step = (int64_t)(rows_per_step / p.group) * p.q.st + (int64_t)dg * p.q.sh;
+    wrap = p.q.st - (int64_t)p.group * p.q.sh;
+  }
+  __device__ __forceinline__ const bf16_t* get(const RowsParams& p) const { return r < p.n_rows ? ptr : last; }
+  __device__ __forceinline__ void advance(const RowsParams& p) {
+    r += dr;
+    g += dg;
+    ptr += step;
+    if (g >= p.group) {
+      g -= p.group;
+      ptr += wrap;
+    }
+  }
+};
+struct KeyCursor {
+  const bf16_t *ptr, *last;
+  int64_t j, step;
+  int dj;
+  __device__ __forceinline__ void init(const RowsParams& p, int b, int v, int64_t j0, int chunk_elems, int rows_per_step) {
+    j = j0;
+    dj = rows_per_step;
+    last = key_row(p, b, v, p.L - 1) + chunk_elems;
+    ptr = key_row(p, b, v, j0) + chunk_elems;
+    step = (int64_t)rows_per_step * p.k.st;
+  }
+  __device__ __forceinline__ const bf16_t* get(const RowsParams& p) const { return j < p.L ? ptr : last; }
+  __device__ __forceinline__ void advance(const RowsParams&) {
+    j += dj;
+    ptr += step;
+  }
+};
+template <bool KEYS>
+struct CursorOf { using type = ProbeCursor; };
+template <>
+struct CursorOf<true> { using type = KeyCursor; };
+
 // Grid: kMax / kMass (ceil(L / 256), Hkv, batch); kStats (ceil(r_pad / 256) * n_chunks, Hkv, batch).
 template <int D, int MODE>
-__global__ __launch_bounds__(256) void matrix_reduce_kernel(const RowsParams p) {
+__global__ __launch_bounds__(256, 3) void matrix_reduce_kernel(const RowsParams p) {
   constexpr int KS = D / 16;                 // MFMA steps along the head dimension
   constexpr int KC = D / 8;                  // 16-byte chunks per vector
   constexpr int ROW_BYTES = D * 2;
-  constexpr int PASSES = 32 * KC / 256;      // 16-byte loads per thread per streamed tile
+  constexpr int TR = 32;                     // streamed vectors per LDS tile (64: no faster, twice the LDS)
+  constexpr int PASSES = TR * KC / 256;      // 16-byte loads per thread per streamed tile
   constexpr bool kKeysResident = MODE != kStats;
-  __shared__ __attribute__((aligned(16))) unsigned char tile[2][32 * ROW_BYTES];
+  __shared__ __attribute__((aligned(16))) unsigned char tile[2][TR * ROW_BYTES];
   extern __shared__ float c_lds[];           // kMass: r_pad entries
 
   const int v = blockIdx.y, b = blockIdx.z;
@@ -103,7 +155,6 @@ __global__ __launch_bounds__(256) void matrix_reduce_kernel(const RowsParams p) 
     str_end = str0 + kChunkKeys < p.L ? str0 + kChunkKeys : p.L;
   }
   auto resident_row = [&](int64_t i) { return kKeysResident ? key_row(p, b, v, i) : probe_row(p, b, v, (int)i); };
-  auto streamed_row = [&](int64_t i) { return kKeysResident ? probe_row(p, b, v, (int)i) : key_row(p, b, v, i); };
 
   // ---- resident B operands: lane (c, hh) holds elements 8*hh + 16*kk .. +7 of vectors res + c and res + 32 + c
   const int64_t res = res0 + wave * 64;
@@ -120,15 +171,17 @@ __global__ __launch_bounds__(256) void matrix_reduce_kernel(const RowsParams p) 
   }
 
   // ---- streamed tiles: thread tid moves chunk tid % KC of tile rows (u*256 + tid) / KC
-  u32x4 pre[PASSES];
-  auto fetch = [&](int64_t first) {
+  typename CursorOf<!kKeysResident>::type cur[PASSES];
+#pragma unroll
+  for (int u = 0; u < PASSES; ++u) cur[u].init(p, b, v, str0 + (u * 256 + tid) / KC, 8 * (tid % KC), TR);
+  auto fetch = [&](u32x4 (&pre)[PASSES]) {           // loads the cursors' tile and moves them to the next one
 #pragma unroll
     for (int u = 0; u < PASSES; ++u) {
-      const int row = (u * 256 + tid) / KC;
-      pre[u] = *reinterpret_cast<const u32x4*>(streamed_row(first + row) + 8 * (tid % KC));
+      pre[u] = *reinterpret_cast<const u32x4*>(cur[u].get(p));
+      cur[u].advance(p);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](const u32x4 (&pre)[PASSES], int buf) {
 #pragma unroll
     for (int u = 0; u < PASSES; ++u) {
       const int row = (u * 256 + tid) / KC;
@@ -143,23 +196,36 @@ __global__ __launch_bounds__(256) void matrix_reduce_kernel(const RowsParams p) 
     z_run[s] = 0.f;
   }
 
-  fetch(str0);
-  stash(0);
-  __syncthreads();
-  int buf = 0;
-  for (int64_t t0 = str0; t0 < str_end; t0 += 32, buf ^= 1) {
-    const bool more = t0 + 32 < str_end;
-    if (more) fetch(t0 + 32);
+  // per 32 streamed vectors: 16 MFMAs per wave and the mode's reduction of the two accumulators
+  auto compute = [&](const int64_t tile0, const int buf) {
+#pragma unroll
+    for (int sub = 0; sub < TR / 32; ++sub) {
+    const int64_t t0 = tile0 + 32 * sub;
+    if (t0 >= str_end) break;
     f32x16 acc[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[s][i] = 0.f;
+    // A fragments are read RA steps at a time ahead of the MFMAs that use them, which then run back to back (order
+    // pinned: left alone, the scheduler sinks every LDS read next to its use and the wave waits out each read's
+    // latency in turn).  The exp-bearing modes have fewer registers to spare.
+    constexpr int RA = 4;
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&tile[buf][c * ROW_BYTES + 16 * ((2 * kk + hh) ^ swz(c))]);
-      acc[0] = mfma(a, rf[0][kk], acc[0]);
-      acc[1] = mfma(a, rf[1][kk], acc[1]);
+    for (int k0 = 0; k0 < KS; k0 += RA) {
+      bf16x8 af[RA];
+#pragma unroll
+      for (int kk = 0; kk < RA; ++kk)
+        af[kk] = *reinterpret_cast<const bf16x8*>(&tile[buf][(32 * sub + c) * ROW_BYTES + 16 * ((2 * (k0 + kk) + hh) ^ swz(c))]);
+#pragma unroll
+      for (int kk = 0; kk < RA; ++kk) {
+        acc[0] = mfma(af[kk], rf[0][k0 + kk], acc[0]);
+        acc[1] = mfma(af[kk], rf[1][k0 + kk], acc[1]);
+      }
+      if (MODE != kStats) {      // (the statistics pass has no registers to spare for a pinned read-ahead)
+        __builtin_amdgcn_sched_group_barrier(0x100, RA, 0);        // RA LDS reads
+        __builtin_amdgcn_sched_group_barrier(0x008, 2 * RA, 0);    // 2*RA MFMAs
+      }
     }
     // the accumulator's register axis runs over the streamed vectors t0 + acc_row(i, hh)
     if (MODE == kMax) {
@@ -200,8 +266,46 @@ __global__ __launch_bounds__(256) void matrix_reduce_kernel(const RowsParams p) 
         red[s] = m_new;
       }
     }
-    if (more) stash(buf ^ 1);
+    }
+  };
+
+  // Tiles travel global -> registers -> LDS two tiles ahead of the MFMAs: while tile t is computed, tile t+1 is
+  // in registers on its way to the other LDS buffer and the loads of tile t+2 are in flight (one tile ahead
+  // leaves only one tile's compute time to cover the L2 latency, and the barrier makes every wave wait for the
+  // slowest load).  Two register sets alternate, so the loop is written out for an even and an odd tile.
+  // (The statistics pass keeps more values live; with two register sets it spills at three waves per SIMD, so it
+  // prefetches one tile ahead only.)
+  constexpr bool kTwoAhead = MODE != kStats;
+  u32x4 pa[PASSES], pb[kTwoAhead ? PASSES : 1];
+  fetch(pa);
+  stash(pa, 0);
+  // everything loaded so far (the resident operands, the first tile) has arrived: vmcnt 0, said with the builtin
+  // so that the compiler's own wait-count bookkeeping knows it
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  if constexpr (kTwoAhead) {
+    if (str0 + TR < str_end) fetch(pa);
     __syncthreads();
+    for (int64_t tile0 = str0; tile0 < str_end; tile0 += 2 * TR) {
+      if (tile0 + 2 * TR < str_end) fetch(pb);
+      compute(tile0, 0);
+      if (tile0 + TR >= str_end) break;
+      stash(pa, 1);
+      __syncthreads();
+      if (tile0 + 3 * TR < str_end) fetch(pa);
+      compute(tile0 + TR, 1);
+      if (tile0 + 2 * TR < str_end) stash(pb, 0);
+      __syncthreads();
+    }
+  } else {
+    __syncthreads();
+    int buf = 0;
+    for (int64_t tile0 = str0; tile0 < str_end; tile0 += TR, buf ^= 1) {
+      const bool more = tile0 + TR < str_end;
+      if (more) fetch(pa);
+      compute(tile0, buf);
+      if (more) stash(pa, buf ^ 1);
+      __syncthreads();
+    }
   }
 
   // ---- the two lane halves hold disjoint streamed vectors for the same resident vector
