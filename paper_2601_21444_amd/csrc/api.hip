@@ -174,7 +174,7 @@ const char* apbv_status_string(apbv_status s) {
   return "unknown apbv_status";
 }
 
-int apbv_version(void) { return 100; }
+int apbv_version(void) { return 200; }
 
 size_t apbv_compress_workspace_bytes(int batch, int n_kv_heads, int head_dim, int64_t L, int64_t l_p) {
   if (batch < 1 || n_kv_heads < 1 || (head_dim != 64 && head_dim != 128) || L < 1 || L > kMaxTokens || l_p < 0 || l_p > L)

@@ -552,7 +552,9 @@ __global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32
   *reinterpret_cast<u32x4*>(v_c + dst) = vv;
 }
 
-std::once_flag g_attr_once;
+// the LDS-size attribute of the selection kernel is a per-device property of the loaded code object
+constexpr int kMaxDevices = 64;
+std::once_flag g_attr_once[kMaxDevices];
 
 }  // namespace
 
@@ -598,7 +600,9 @@ apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
                          w.n_sort, p.idx_out, reinterpret_cast<uint64_t*>(ws + w.sort_keys_off),
                          reinterpret_cast<uint32_t*>(ws + w.sort_idx_off), p.hkv);
     } else {
-      std::call_once(g_attr_once, [] {
+      int device = 0;
+      (void)hipGetDevice(&device);
+      std::call_once(g_attr_once[device & (kMaxDevices - 1)], [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsSortMax * 14));
       });
