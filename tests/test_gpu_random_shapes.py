@@ -77,3 +77,32 @@ def test_random_shapes_all_attention_entry_points(seed):
         assert torch.equal(res[2].view(torch.int16), out.view(torch.int16))
         ref2, _ = oracle.host_attention(*other, scale)
         check(to_f64(res[1]), ref2, "group, second problem")
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_shapes_compress_bit_exact(seed):
+    """Seeded random shapes through apbv_compress_kv: ragged block lengths around the kernels' row groupings, every
+    l_p from 0 to L, both head dimensions, quantised keys (many exact ties) in half of the cases."""
+    rng = np.random.default_rng((72, seed))
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 4]))
+    hq = hkv * int(rng.choice([1, 3, 8]))
+    n_q = int(rng.choice([1, 2, 7, 64, 130]))
+    L = int(rng.choice([1, 2, 63, 64, 65, 255, 1000, 4097, 20000]))
+    l_p = int(rng.choice([0, 1, L // 3, L - 1, L])) if L > 1 else int(rng.choice([0, 1]))
+    l_p = max(0, min(l_p, L))
+    qp = rand_bits(rng, (n_q, hq, d))
+    if seed % 2:
+        k = wl.f32_to_bf16_bits(rng.integers(-2, 3, size=(L, hkv, d)).astype(np.float32))     # few distinct scores
+    else:
+        k = rand_bits(rng, (L, hkv, d))
+    v = rand_bits(rng, (L, hkv, d))
+    print(f"random compress seed={seed}: hq={hq} hkv={hkv} d={d} n_q={n_q} L={L} l_p={l_p}", flush=True)
+    idx, k_c, v_c, s = apbv.apbv_compress_kv(dev(qp), dev(k), dev(v), l_p, return_scores=True)
+    torch.cuda.synchronize()
+    idx_r, kc_r, vc_r, s_r = oracle.compress_kv(qp, k, v, l_p)
+    np.testing.assert_allclose(s.cpu().numpy(), s_r, rtol=1e-12, atol=1e-9)
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx_r)
+    bits_of = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    np.testing.assert_array_equal(bits_of(k_c), kc_r)
+    np.testing.assert_array_equal(bits_of(v_c), vc_r)
