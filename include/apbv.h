@@ -9,6 +9,9 @@
  *                        gather them into the compressed block (K_c, V_c).
  *   apbv_host_attention  Eq. 4 (with Eq. 1): attention of the local query block over the concatenation
  *                        [anchor | passing | local], anchor and passing fully visible, local causal.
+ * Around them: apbv_host_attention_group (the attention problems of a physical host's two virtual hosts and of the
+ * anchor block in one launch, Sec. 4.3) and apbv_compress_kv_reduced (the compression under another reduction of
+ * the score matrix to one score per key).
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer (HIP global memory on the current device) unless a
@@ -16,7 +19,8 @@
  *   - The caller owns every buffer (inputs, outputs, workspace).  The library allocates no device
  *     memory and keeps no state between calls.
  *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
- *     the default stream) and outputs are valid once the caller has synchronised that stream.
+ *     the default stream) and outputs are valid once the caller has synchronised that stream.  The calls can be
+ *     captured into a HIP graph (they enqueue kernels only).
  *   - Inputs are never written.  Outputs and workspace must not overlap inputs or each other.
  *   - Every argument error is detected on the host before anything is launched and reported through
  *     the return value; nothing is launched in that case.  No function throws or aborts.
