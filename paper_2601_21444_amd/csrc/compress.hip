@@ -153,10 +153,8 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
   const int v = blockIdx.y, b = blockIdx.z;
   const int c = threadIdx.x % LPR;
   const int rsub = threadIdx.x / LPR;
-  const double* qb = qbar + ((int64_t)b * hkv + v) * D + 8 * c;
-  double qv[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) qv[e] = qb[e];
+  __shared__ double qs[D];
+  const double* qb = qbar + ((int64_t)b * hkv + v) * D;
   const bf16_t* base = k.ptr + (int64_t)b * k.sb + (int64_t)v * k.sh + 8 * c;
   const int64_t out_base = ((int64_t)b * hkv + v) * L;
   const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
@@ -171,6 +169,19 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
       if (j < r_end) z = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + j * k.st));
       x[u] = z;
     }
+    // The pooled query reaches the lanes through LDS -- one 16-byte load by D/2 lanes per workgroup, behind the
+    // key loads, instead of four loads per lane in front of them.
+    if (r0 == r_begin) {
+      if (threadIdx.x < D / 2) {
+        const double2 t = *reinterpret_cast<const double2*>(qb + 2 * threadIdx.x);
+        qs[2 * threadIdx.x] = t.x;
+        qs[2 * threadIdx.x + 1] = t.y;
+      }
+      __syncthreads();
+    }
+    double qv[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qv[e] = qs[8 * c + e];
     double a[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
