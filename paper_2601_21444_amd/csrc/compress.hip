@@ -559,8 +559,9 @@ __global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32
   const int64_t dst = (((int64_t)b * l_p + i) * hkv + head) * D + 8 * c;
   const u32x4 kk = *reinterpret_cast<const u32x4*>(k.ptr + (int64_t)b * k.sb + j * k.st + (int64_t)head * k.sh + 8 * c);
   const u32x4 vv = *reinterpret_cast<const u32x4*>(v.ptr + (int64_t)b * v.sb + j * v.st + (int64_t)head * v.sh + 8 * c);
-  *reinterpret_cast<u32x4*>(k_c + dst) = kk;
-  *reinterpret_cast<u32x4*>(v_c + dst) = vv;
+  // (the compressed block is written once and read by another kernel or a copy engine: keep it out of the caches)
+  __builtin_nontemporal_store(kk, reinterpret_cast<u32x4*>(k_c + dst));
+  __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(v_c + dst));
 }
 
 // the LDS-size attribute of the selection kernel is a per-device property of the loaded code object
