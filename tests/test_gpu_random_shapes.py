@@ -106,3 +106,23 @@ def test_random_shapes_compress_bit_exact(seed):
     bits_of = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
     np.testing.assert_array_equal(bits_of(k_c), kc_r)
     np.testing.assert_array_equal(bits_of(v_c), vc_r)
+
+
+@pytest.mark.parametrize("gain", [8.0, 40.0])
+def test_attention_with_peaked_logits(gain):
+    """Queries scaled up so that the softmax is nearly one-hot and the running maximum jumps by far more than the
+    lazy-rescale threshold from tile to tile (scaled logits up to several hundred): no overflow, same tolerances."""
+    rng = np.random.default_rng((73, int(gain)))
+    hq, hkv, d, L, l_a, n_p = 4, 2, 128, 300, 200, 500
+    scale = 1.0 / math.sqrt(d)
+    q = wl.f32_to_bf16_bits((rng.standard_normal((L, hq, d)) * gain).astype(np.float32))
+    ka, va, kp, vp, k, v = (rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_p, n_p, L, L))
+    # ascending key norms along the key axis make the maximum grow again and again
+    grow = np.linspace(0.2, 2.0, n_p, dtype=np.float32)[:, None, None]
+    kp = wl.f32_to_bf16_bits(wl.bf16_bits_to_f32(kp) * grow)
+    out, lse = apbv.apbv_host_attention(*[dev(x) for x in (q, ka, va, kp, vp, k, v)], scale, return_lse=True)
+    torch.cuda.synchronize()
+    ref, lse_r = oracle.host_attention(q, ka, va, kp, vp, k, v, scale)
+    print(f"peaked logits gain={gain}: lse range {lse_r.min():.1f} .. {lse_r.max():.1f}", flush=True)
+    check(to_f64(out), ref, f"peaked logits x{gain}")
+    np.testing.assert_allclose(lse.cpu().numpy().astype(np.float64), lse_r, rtol=2e-5, atol=2e-3)
