@@ -17,10 +17,13 @@
  *   - Every data pointer is a DEVICE pointer (HIP global memory on the current device) unless a
  *     parameter is explicitly marked host.  bf16 values are passed as their 16-bit patterns.
  *   - The caller owns every buffer (inputs, outputs, workspace).  The library allocates no device
- *     memory and keeps no state between calls.
+ *     memory.  Its only state is a per-device one-time set-up made by the first compression call on a device
+ *     (apbv_compress_kv, apbv_compress_kv_reduced): a function attribute of the selection kernel.  No results
+ *     depend on it.
  *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and outputs are valid once the caller has synchronised that stream.  The calls can be
- *     captured into a HIP graph (they enqueue kernels only).
+ *     captured into a HIP graph (they enqueue kernels only); make the first compression call on a device before
+ *     the capture starts, so that the one-time set-up is not part of it.
  *   - Inputs are never written.  Outputs and workspace must not overlap inputs or each other.
  *   - Every argument error is detected on the host before anything is launched and reported through
  *     the return value; nothing is launched in that case.  No function throws or aborts.

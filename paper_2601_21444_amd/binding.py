@@ -126,6 +126,23 @@ def tensor_view(t: torch.Tensor) -> Tuple[ApbvTensor, int]:
     return view, b
 
 
+def _check_buffer(t: Optional[torch.Tensor], name: str, dtype: torch.dtype, shape, device) -> None:
+    """A caller-supplied output or workspace must be a dense device tensor of the right type holding at least the
+    elements the library will write (``shape``: the dense shape, or a minimum element count) -- its pointer goes to
+    the C ABI unchecked beyond that."""
+    if t is None:
+        return
+    need = int(shape) if isinstance(shape, int) else int(torch.Size(shape).numel())
+    if not isinstance(t, torch.Tensor) or t.dtype != dtype:
+        raise TypeError(f"{name}: expected a {dtype} tensor")
+    if not t.is_cuda or t.device != device:
+        raise ValueError(f"{name}: must live on {device}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    if t.numel() < need:
+        raise ValueError(f"{name}: holds {t.numel()} elements, {need} are written")
+
+
 def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
     s = stream if stream is not None else torch.cuda.current_stream()
     return int(s.cuda_stream)
@@ -159,6 +176,11 @@ def apbv_compress_kv(q_probe: torch.Tensor, k_local: torch.Tensor, v_local: torc
     hq, d = q_probe.shape[-2], q_probe.shape[-1]
     hkv, L = k_local.shape[-2], k_local.shape[-3]
     dev = k_local.device
+    _check_buffer(idx_out, "idx_out", torch.int32, (b, hkv, l_p), dev)
+    _check_buffer(k_c_out, "k_c_out", torch.bfloat16, (b, l_p, hkv, d), dev)
+    _check_buffer(v_c_out, "v_c_out", torch.bfloat16, (b, l_p, hkv, d), dev)
+    _check_buffer(scores_out, "scores_out", torch.float64, (b, hkv, L), dev)
+    _check_buffer(workspace, "workspace", torch.uint8, 0, dev)
     if idx_out is None:
         idx_out = torch.empty((b, hkv, l_p), dtype=torch.int32, device=dev)
     if k_c_out is None:
@@ -208,6 +230,8 @@ def apbv_host_attention(q_local: torch.Tensor, k_anchor: torch.Tensor, v_anchor:
     L, hq, d = q_local.shape[-3], q_local.shape[-2], q_local.shape[-1]
     hkv = k_anchor.shape[-2]
     dev = q_local.device
+    _check_buffer(out, "out", torch.bfloat16, (b, L, hq, d), dev)
+    _check_buffer(lse_out, "lse_out", torch.float32, (b, hq, L), dev)
     if out is None:
         out = torch.empty((b, L, hq, d), dtype=torch.bfloat16, device=dev)
     if return_lse and lse_out is None:
@@ -249,6 +273,8 @@ def apbv_host_attention_group(problems, softmax_scale: float, *, return_lse: boo
             hq, hkv, d = hq_m, hkv_m, d_m
         elif (hq_m, hkv_m, d_m) != (hq, hkv, d):
             raise ValueError("all problems of a group share the head counts and head_dim")
+        _check_buffer(out, "out", torch.bfloat16, (L, hq, d), q.device)
+        _check_buffer(lse, "lse_out", torch.float32, (hq, L), q.device)
         if out is None:
             out = torch.empty((L, hq, d), dtype=torch.bfloat16, device=q.device)
         if return_lse and lse is None:
@@ -291,6 +317,9 @@ def apbv_query_attention(q_block: torch.Tensor, k_anchor: torch.Tensor, v_anchor
     hkv = k_anchor.shape[-2]
     n_keys = k_anchor.shape[-3] + k_pass.shape[-3] + k_local.shape[-3]
     dev = q_block.device
+    _check_buffer(out, "out", torch.bfloat16, (b, n_q, hq, d), dev)
+    _check_buffer(lse_out, "lse_out", torch.float32, (b, hq, n_q), dev)
+    _check_buffer(workspace, "workspace", torch.uint8, 0, dev)
     if out is None:
         out = torch.empty((b, n_q, hq, d), dtype=torch.bfloat16, device=dev)
     if return_lse and lse_out is None:
@@ -324,6 +353,8 @@ def apbv_merge_lse(parts_out: torch.Tensor, parts_lse: torch.Tensor, *, return_l
         raise ValueError("parts_lse must be [n_parts, Hq, rows]")
     if not parts_out[0].is_contiguous() or not parts_lse[0].is_contiguous():
         raise ValueError("each part must be dense")
+    _check_buffer(out, "out", torch.bfloat16, (rows, hq, d), parts_out.device)
+    _check_buffer(lse_out, "lse_out", torch.float32, (hq, rows), parts_out.device)
     if out is None:
         out = torch.empty((rows, hq, d), dtype=torch.bfloat16, device=parts_out.device)
     if return_lse and lse_out is None:

@@ -2,8 +2,11 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <tuple>
+#include <utility>
 #include "apbv.h"
 #include "attention_schedule.h"
+#include "host_validation.h"
 
 namespace apbv {
 
@@ -15,6 +18,32 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;               // 16 bytes
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;               // 8 bytes
+
+// Kernel launches of one entry point.  The status kept is that of THESE launches, as returned by the launch call
+// itself: hipGetLastError() would also return -- and clear -- an error left behind by an unrelated earlier runtime
+// call of the thread.  After a refused launch nothing further is launched.
+class Launcher {
+ public:
+  explicit Launcher(hipStream_t stream) : stream_(stream) {}
+  template <typename... P, typename... A>
+  void operator()(void (*kernel)(P...), dim3 grid, dim3 block, size_t lds_bytes, A&&... args) {
+    static_assert(sizeof...(P) == sizeof...(A), "one argument per kernel parameter");
+    if (err_ != hipSuccess) return;
+    std::tuple<P...> vals(static_cast<P>(args)...);          // each argument in its parameter's exact type
+    err_ = launch(reinterpret_cast<const void*>(kernel), grid, block, lds_bytes, vals, std::index_sequence_for<P...>{});
+  }
+  bool ok() const { return err_ == hipSuccess; }
+  apbv_status status() const { return err_ == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH; }
+
+ private:
+  template <typename Tuple, size_t... I>
+  hipError_t launch(const void* fn, dim3 grid, dim3 block, size_t lds_bytes, Tuple& vals, std::index_sequence<I...>) {
+    void* ptrs[] = {static_cast<void*>(&std::get<I>(vals))...};
+    return hipLaunchKernel(fn, grid, block, ptrs, lds_bytes, stream_);
+  }
+  hipStream_t stream_;
+  hipError_t err_ = hipSuccess;
+};
 
 // A [tokens, heads, d] bf16 view already offset to nothing: base pointer plus element strides.
 struct View {
@@ -53,10 +82,6 @@ struct AttnParams {
   int n_splits, tiles_per_split;
   int64_t split_stride_out, split_stride_lse;
 };
-constexpr int kAttnKeyTile = 64;      // keys per tile of the attention kernel
-constexpr int kAttnQueryTile = 256;   // query rows per workgroup
-constexpr int kAttnNarrowQueryTile = 64;    // ... of the variant used for query blocks of at most
-constexpr int kAttnNarrowMaxRows = 128;     // this many rows
 
 apbv_status launch_host_attention(const AttnParams& p, int head_dim, hipStream_t stream);
 
@@ -103,6 +128,7 @@ struct CompressParams {
 size_t compress_workspace_bytes(int batch, int hkv, int d, int64_t L, int64_t l_p);
 size_t matrix_scores_workspace_bytes(int reducer, int batch, int hkv, int64_t n_rows, int64_t L);
 apbv_status launch_compress(const CompressParams& p, hipStream_t stream);
+apbv_status check_matrix_scores(const CompressParams& p);
 apbv_status launch_matrix_scores(const CompressParams& p, double* scores, void* stats_ws, hipStream_t stream);
 
 }  // namespace apbv

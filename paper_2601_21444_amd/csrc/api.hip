@@ -7,53 +7,14 @@ using namespace apbv;
 
 namespace {
 
-constexpr int64_t kMaxTokens = (int64_t)1 << 24;
-
-bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
-
-// A view is acceptable if it is empty, or has a 16-byte aligned pointer and strides that keep every
-// (token, head) row 16-byte aligned and non-overlapping along the head dimension.
-apbv_status check_view(const apbv_tensor& t, int heads, int d, int batch, bool may_be_empty) {
-  if (t.tokens < 0 || t.tokens > kMaxTokens) return APBV_ERR_SHAPE;
-  if (t.tokens == 0) return may_be_empty ? APBV_OK : APBV_ERR_SHAPE;
-  if (t.ptr == nullptr) return APBV_ERR_NULL;
-  if (!aligned(t.ptr, 16)) return APBV_ERR_SHAPE;
-  if (t.stride_token < d || t.stride_token % 8) return APBV_ERR_SHAPE;
-  if (t.stride_token >= kMaxTokens) return APBV_ERR_UNSUPPORTED;       // the kernels keep row offsets of a 64-row tile in 32 bits
-  if (heads > 1 && (t.stride_head < d || t.stride_head % 8)) return APBV_ERR_SHAPE;
-  if (batch > 1 && (t.stride_batch <= 0 || t.stride_batch % 8)) return APBV_ERR_SHAPE;
-  return APBV_OK;
-}
-
-apbv_status check_heads(int batch, int hq, int hkv, int d) {
-  if (batch < 1 || hq < 1 || hkv < 1 || batch > 65535 || hq > 65535) return APBV_ERR_SHAPE;
-  if (hq % hkv) return APBV_ERR_SHAPE;
-  if (d != 64 && d != 128) return APBV_ERR_UNSUPPORTED;
-  return APBV_OK;
-}
-
-constexpr int kMaxKeySplits = 256;
-
 // Validation shared by the two attention entry points; fills everything of `p` but the key split.
 apbv_status fill_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_local,
                                   apbv_tensor k_anchor, apbv_tensor v_anchor, apbv_tensor k_pass, apbv_tensor v_pass,
                                   apbv_tensor k_local, apbv_tensor v_local, float softmax_scale, void* out,
                                   float* lse_out, AttnParams& p) {
-  apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
+  const apbv_status st = validate_attention(batch, n_q_heads, n_kv_heads, head_dim, q_local, k_anchor, v_anchor, k_pass,
+                                            v_pass, k_local, v_local, softmax_scale, out, lse_out);
   if (st != APBV_OK) return st;
-  if ((st = check_view(q_local, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if ((st = check_view(k_anchor, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if ((st = check_view(v_anchor, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if ((st = check_view(k_pass, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if ((st = check_view(v_pass, n_kv_heads, head_dim, batch, true)) != APBV_OK) return st;
-  if ((k_local.tokens != 0 && q_local.tokens != k_local.tokens) || v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
-  if (v_anchor.tokens != k_anchor.tokens || v_pass.tokens != k_pass.tokens) return APBV_ERR_SHAPE;
-  if (k_anchor.tokens + k_pass.tokens + k_local.tokens < 1) return APBV_ERR_SHAPE;       // every query needs a key
-  if (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale)) return APBV_ERR_SHAPE;
-  if (out == nullptr) return APBV_ERR_NULL;
-  if (!aligned(out, 16) || (lse_out != nullptr && !aligned(lse_out, 4))) return APBV_ERR_SHAPE;
 
   p.q = to_view(q_local);
   p.k_seg[0] = to_view(k_anchor);
@@ -79,33 +40,6 @@ apbv_status fill_attention(int batch, int n_q_heads, int n_kv_heads, int head_di
   return APBV_OK;
 }
 
-// Key split of the query-block attention: how many ranges of how many 64-key tiles.  With `requested` == 0 the
-// count is chosen so that (query tiles x heads x batch x splits) reaches about two workgroups per compute unit
-// while every range keeps at least four tiles; ranges are equal and none is empty.
-struct KeySplit {
-  int n_splits, tiles_per_split;
-};
-KeySplit plan_key_split(int batch, int n_q_heads, int64_t n_q, int64_t n_keys, int requested) {
-  const int64_t n_tiles = (n_keys + kAttnKeyTile - 1) / kAttnKeyTile;
-  int64_t s = requested;
-  if (s <= 0) {
-    const int64_t tile = n_q <= kAttnNarrowMaxRows ? kAttnNarrowQueryTile : kAttnQueryTile;
-    const int64_t wgs = (n_q + tile - 1) / tile * n_q_heads * batch;
-    s = (512 + wgs - 1) / wgs;
-    const int64_t cap = n_tiles / 4 > 1 ? n_tiles / 4 : 1;
-    s = s < cap ? s : cap;
-  }
-  s = s < n_tiles ? s : n_tiles;
-  s = s < kMaxKeySplits ? s : kMaxKeySplits;
-  const int64_t per = (n_tiles + s - 1) / s;
-  KeySplit ks;
-  ks.tiles_per_split = (int)per;
-  ks.n_splits = (int)((n_tiles + per - 1) / per);
-  return ks;
-}
-
-size_t align256(size_t x) { return (x + 255) / 256 * 256; }
-
 size_t reduced_workspace_bytes(int reducer, int batch, int hq, int hkv, int d, int64_t n_q, int64_t L, int64_t l_p) {
   const size_t base = compress_workspace_bytes(batch, hkv, d, L, l_p);
   if (reducer == APBV_REDUCE_SUM) return base;
@@ -116,22 +50,10 @@ apbv_status compress_entry(int reducer, float softmax_scale, int batch, int n_q_
                              apbv_tensor k_local, apbv_tensor v_local, int64_t l_p, int32_t* idx_out, void* k_c_out,
                              void* v_c_out, double* scores_out, void* workspace, size_t workspace_bytes,
                              void* hip_stream) {
-  apbv_status st = check_heads(batch, n_q_heads, n_kv_heads, head_dim);
+  const apbv_status st = validate_compress(reducer, softmax_scale, batch, n_q_heads, n_kv_heads, head_dim, q_probe, k_local,
+                                           v_local, l_p, idx_out, k_c_out, v_c_out, scores_out);
   if (st != APBV_OK) return st;
-  if ((st = check_view(q_probe, n_q_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(k_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if ((st = check_view(v_local, n_kv_heads, head_dim, batch, false)) != APBV_OK) return st;
-  if (v_local.tokens != k_local.tokens) return APBV_ERR_SHAPE;
   const int64_t L = k_local.tokens;
-  if (l_p < 0 || l_p > L) return APBV_ERR_SHAPE;
-  if (l_p > 0) {
-    if (idx_out == nullptr || k_c_out == nullptr || v_c_out == nullptr) return APBV_ERR_NULL;
-    if (!aligned(k_c_out, 16) || !aligned(v_c_out, 16) || !aligned(idx_out, 4)) return APBV_ERR_SHAPE;
-  }
-  if (scores_out != nullptr && !aligned(scores_out, 8)) return APBV_ERR_SHAPE;
-  if (reducer != APBV_REDUCE_SUM && reducer != APBV_REDUCE_MAX && reducer != APBV_REDUCE_SOFTMAX_SUM) return APBV_ERR_SHAPE;
-  if (q_probe.tokens * (n_q_heads / n_kv_heads) > (int64_t)1 << 24) return APBV_ERR_UNSUPPORTED;   // rows of the score matrix per KV head
-  if (reducer == APBV_REDUCE_SOFTMAX_SUM && (!(softmax_scale > 0.0f) || !std::isfinite(softmax_scale))) return APBV_ERR_SHAPE;
   const size_t need = reduced_workspace_bytes(reducer, batch, n_q_heads, n_kv_heads, head_dim, q_probe.tokens, L, l_p);
   if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) return APBV_ERR_WORKSPACE;
 
@@ -177,9 +99,7 @@ const char* apbv_status_string(apbv_status s) {
 int apbv_version(void) { return 200; }
 
 size_t apbv_compress_workspace_bytes(int batch, int n_kv_heads, int head_dim, int64_t L, int64_t l_p) {
-  if (batch < 1 || n_kv_heads < 1 || (head_dim != 64 && head_dim != 128) || L < 1 || L > kMaxTokens || l_p < 0 || l_p > L)
-    return 0;
-  return compress_workspace_bytes(batch, n_kv_heads, head_dim, L, l_p);
+  return compress_workspace_bytes_checked(batch, n_kv_heads, head_dim, L, l_p);
 }
 
 apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_probe,
@@ -195,7 +115,7 @@ size_t apbv_compress_reduced_workspace_bytes(int reducer, int batch, int n_q_hea
   if (batch < 1 || n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads || (head_dim != 64 && head_dim != 128) ||
       n_q < 1 || n_q > kMaxTokens || L < 1 || L > kMaxTokens || l_p < 0 || l_p > L)
     return 0;
-  if (reducer != APBV_REDUCE_SUM && reducer != APBV_REDUCE_MAX && reducer != APBV_REDUCE_SOFTMAX_SUM) return 0;
+  if (!valid_reducer(reducer)) return 0;
   return reduced_workspace_bytes(reducer, batch, n_q_heads, n_kv_heads, head_dim, n_q, L, l_p);
 }
 
@@ -237,13 +157,7 @@ apbv_status apbv_host_attention_group(int n_items, const apbv_attention_item* it
 
 size_t apbv_query_attention_workspace_bytes(int batch, int n_q_heads, int head_dim, int64_t n_q, int64_t n_keys,
                                             int n_splits) {
-  if (batch < 1 || n_q_heads < 1 || (head_dim != 64 && head_dim != 128) || n_q < 1 || n_keys < 1 || n_splits < 0 ||
-      n_q > kMaxTokens || n_keys > 3 * kMaxTokens)
-    return 0;
-  const KeySplit ks = plan_key_split(batch, n_q_heads, n_q, n_keys, n_splits);
-  if (ks.n_splits == 1) return 0;
-  const size_t rows = (size_t)batch * (size_t)n_q * (size_t)n_q_heads;
-  return (size_t)ks.n_splits * (align256(rows * head_dim * sizeof(bf16_t)) + align256(rows * sizeof(float)));
+  return query_attention_workspace_bytes(batch, n_q_heads, head_dim, n_q, n_keys, n_splits);
 }
 
 apbv_status apbv_query_attention(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_block,
@@ -296,16 +210,9 @@ apbv_status apbv_query_attention(int batch, int n_q_heads, int n_kv_heads, int h
 apbv_status apbv_merge_lse(int n_parts, int64_t rows, int n_q_heads, int head_dim, const void* parts_out,
                            int64_t part_stride_out, const float* parts_lse, int64_t part_stride_lse, void* out,
                            float* lse_out, void* hip_stream) {
-  if (n_parts < 1 || n_parts > 65536 || rows < 1 || rows > kMaxTokens || n_q_heads < 1 || n_q_heads > 65535)
-    return APBV_ERR_SHAPE;
-  if (head_dim != 64 && head_dim != 128) return APBV_ERR_UNSUPPORTED;
-  if (parts_out == nullptr || parts_lse == nullptr || out == nullptr) return APBV_ERR_NULL;
-  if (!aligned(parts_out, 16) || !aligned(out, 16) || !aligned(parts_lse, 4) || (lse_out != nullptr && !aligned(lse_out, 4)))
-    return APBV_ERR_SHAPE;
-  if (n_parts > 1) {
-    if (part_stride_out < rows * n_q_heads * head_dim || part_stride_out % 8) return APBV_ERR_SHAPE;
-    if (part_stride_lse < rows * n_q_heads) return APBV_ERR_SHAPE;
-  }
+  const apbv_status st = validate_merge(n_parts, rows, n_q_heads, head_dim, parts_out, part_stride_out, parts_lse,
+                                        part_stride_lse, out, lse_out);
+  if (st != APBV_OK) return st;
   MergeParams p;
   p.parts_out = static_cast<const bf16_t*>(parts_out);
   p.parts_lse = parts_lse;

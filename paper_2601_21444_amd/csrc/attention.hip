@@ -97,10 +97,10 @@ __device__ __forceinline__ const char* uniform_ptr(const char* p) {      // a wa
 }
 __device__ __forceinline__ void dma16_uniform(const char* base_uniform, uint32_t lane_off, uint32_t lds_dst) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_dst), "v"(lane_off), "s"(base_uniform)
-               : "memory");
+               : "memory", "m0");
 }
 __device__ __forceinline__ void dma16_lane(const char* addr, uint32_t lds_dst) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_dst), "v"(addr) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_dst), "v"(addr) : "memory", "m0");
 }
 __device__ __forceinline__ uint32_t lds_addr(const unsigned char* p) { return (uint32_t)(size_t)(APBV_LDS(const unsigned char))p; }
 
@@ -199,6 +199,8 @@ __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const i
   __shared__ __attribute__((aligned(1024))) unsigned char k_lds1[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds0[T::TILE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char v_lds1[T::TILE_BYTES];
+  // the LDS destination of an LDS-direct load travels in M0, which addresses the first 64 KB of the workgroup's LDS
+  static_assert(4 * T::TILE_BYTES <= 65536, "the four K/V tiles must lie below 64 KB of LDS");
   const int h = kvh * p.group + g;
 
   const int tid = threadIdx.x;
@@ -472,13 +474,14 @@ static apbv_status launch_variant(const AttnParams& p, int head_dim, hipStream_t
   if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_blocks);
   dim3 block(64 * W);
+  Launcher launch(stream);
   if (head_dim == 128)
-    hipLaunchKernelGGL((host_attention_kernel<128, W>), grid, block, 0, stream, p, n_qtiles, (int)n_items);
+    launch(host_attention_kernel<128, W>, grid, block, 0, p, n_qtiles, (int)n_items);
   else if (head_dim == 64)
-    hipLaunchKernelGGL((host_attention_kernel<64, W>), grid, block, 0, stream, p, n_qtiles, (int)n_items);
+    launch(host_attention_kernel<64, W>, grid, block, 0, p, n_qtiles, (int)n_items);
   else
     return APBV_ERR_UNSUPPORTED;
-  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+  return launch.status();
 }
 
 // Query blocks of at most kAttnNarrowMaxRows rows take the 64-row workgroups: a 256-row tile would compute mostly
@@ -507,13 +510,14 @@ apbv_status launch_host_attention_group(AttnGroupParams& gp, int head_dim, hipSt
   if (n_blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
   dim3 grid((unsigned)n_blocks);
   dim3 block(64 * kWaves);
+  Launcher launch(stream);
   if (head_dim == 128)
-    hipLaunchKernelGGL(host_attention_group_kernel<128>, grid, block, 0, stream, gp);
+    launch(host_attention_group_kernel<128>, grid, block, 0, gp);
   else if (head_dim == 64)
-    hipLaunchKernelGGL(host_attention_group_kernel<64>, grid, block, 0, stream, gp);
+    launch(host_attention_group_kernel<64>, grid, block, 0, gp);
   else
     return APBV_ERR_UNSUPPORTED;
-  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+  return launch.status();
 }
 
 }  // namespace apbv

@@ -20,44 +20,6 @@ namespace apbv {
 namespace {
 
 constexpr int kSelectThreads = 1024;
-constexpr int64_t kLdsSortMax = 8192;          // entries that fit the LDS selection arrays (14 bytes each)
-
-__host__ __device__ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-
-inline int64_t pow2_ceil(int64_t x) {
-  int64_t n = 1;
-  while (n < x) n <<= 1;
-  return n;
-}
-
-struct Workspace {
-  size_t qbar_off, scores_off, sort_keys_off, sort_idx_off, total;
-  int64_t n_sort;       // capacity (entries, a power of two) of the selection's sort arrays
-  bool sort_in_global;
-};
-
-Workspace plan_workspace(int batch, int hkv, int d, int64_t L, int64_t l_p) {
-  Workspace w;
-  size_t off = 0;
-  w.qbar_off = off;
-  off = align_up(off + (size_t)batch * hkv * d * sizeof(double), 256);
-  w.scores_off = off;
-  off = align_up(off + (size_t)batch * hkv * (size_t)L * sizeof(double), 256);
-  // capacity of the sort arrays: room for the candidates of the fast path (the winners plus the rest
-  // of the threshold bucket) when that fits the LDS, else exactly the padded winners
-  w.n_sort = pow2_ceil(l_p > 1 ? l_p : 1);
-  w.sort_in_global = w.n_sort > kLdsSortMax;
-  if (!w.sort_in_global && 2 * w.n_sort <= kLdsSortMax) w.n_sort *= 2;
-  w.sort_keys_off = w.sort_idx_off = off;
-  if (w.sort_in_global) {
-    w.sort_keys_off = off;
-    off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * sizeof(uint64_t), 256);
-    w.sort_idx_off = off;
-    off = align_up(off + (size_t)batch * hkv * (size_t)w.n_sort * (sizeof(uint32_t) + sizeof(uint16_t)), 256);
-  }
-  w.total = off;
-  return w;
-}
 
 __device__ __forceinline__ double bf16_to_f64(uint32_t bits16) {
   return (double)__uint_as_float(bits16 << 16);
@@ -564,22 +526,52 @@ __global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32
   __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(v_c + dst));
 }
 
-// the LDS-size attribute of the selection kernel is a per-device property of the loaded code object
+// Per-device one-time set-up (the library's only state): the selection kernel's dynamic-LDS limit, which is a
+// per-device property of the loaded code object.
 constexpr int kMaxDevices = 64;
-std::once_flag g_attr_once[kMaxDevices];
+struct DeviceState {
+  bool ready = false;
+};
+std::mutex g_state_mutex;
+DeviceState g_state[kMaxDevices];
+
+apbv_status device_state(DeviceState& out) {
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess || device < 0) return APBV_ERR_LAUNCH;
+  if (device >= kMaxDevices) return APBV_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_state_mutex);
+  DeviceState& st = g_state[device];
+  if (!st.ready) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)(kLdsSortMax * 14)) != hipSuccess)
+      return APBV_ERR_LAUNCH;
+    st.ready = true;
+  }
+  out = st;
+  return APBV_OK;
+}
 
 }  // namespace
 
 size_t compress_workspace_bytes(int batch, int hkv, int d, int64_t L, int64_t l_p) {
-  return plan_workspace(batch, hkv, d, L, l_p).total;
+  return plan_compress_workspace(batch, hkv, d, L, l_p).total;
 }
 
-apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
-  const Workspace w = plan_workspace(p.batch, p.hkv, p.d, p.L, p.l_p);
+apbv_status launch_compress(const CompressParams& p_in, hipStream_t stream) {
+  CompressParams p = p_in;
+  const CompressWorkspace w = plan_compress_workspace(p.batch, p.hkv, p.d, p.L, p.l_p);
+  if (p.reducer != APBV_REDUCE_SUM) {
+    const apbv_status ok = check_matrix_scores(p);
+    if (ok != APBV_OK) return ok;
+  }
+  DeviceState dev;
+  const apbv_status ds = device_state(dev);
+  if (ds != APBV_OK) return ds;
   if (p.workspace_bytes < w.total) return APBV_ERR_WORKSPACE;
   unsigned char* ws = static_cast<unsigned char*>(p.workspace);
   double* qbar = reinterpret_cast<double*>(ws + w.qbar_off);
   double* scores = reinterpret_cast<double*>(ws + w.scores_off);
+  Launcher launch(stream);
 
   if (p.reducer != APBV_REDUCE_SUM) {
     // the non-linear reductions form the logit matrix on the matrix cores (score_matrix.hip); their row
@@ -592,45 +584,34 @@ apbv_status launch_compress(const CompressParams& p, hipStream_t stream) {
   } else {
     // pooled query
     if (p.d == 128)
-      hipLaunchKernelGGL(pool_query_kernel<128>, dim3(p.hkv, p.batch), dim3(1024), 0, stream, p.q_probe, p.q_probe.tokens,
-                         p.group, qbar, p.hkv);
+      launch(pool_query_kernel<128>, dim3(p.hkv, p.batch), dim3(1024), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv);
     else
-      hipLaunchKernelGGL(pool_query_kernel<64>, dim3(p.hkv, p.batch), dim3(1024), 0, stream, p.q_probe, p.q_probe.tokens,
-                         p.group, qbar, p.hkv);
+      launch(pool_query_kernel<64>, dim3(p.hkv, p.batch), dim3(1024), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv);
     // scores: one outer iteration per workgroup: 4 rows in flight per thread, many small workgroups
     const int rows_per_block = 4 * 256 / (p.d / 8);
     dim3 grid((unsigned)((p.L + rows_per_block - 1) / rows_per_block), p.hkv, p.batch);
     if (p.d == 128)
-      hipLaunchKernelGGL(score_kernel<128>, grid, dim3(256), 0, stream, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
+      launch(score_kernel<128>, grid, dim3(256), 0, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
     else
-      hipLaunchKernelGGL(score_kernel<64>, grid, dim3(256), 0, stream, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
+      launch(score_kernel<64>, grid, dim3(256), 0, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
   }
   if (p.l_p > 0) {
     // select + order
     if (w.sort_in_global) {
-      hipLaunchKernelGGL(select_kernel<true>, dim3(p.hkv, p.batch), dim3(kSelectThreads), 0, stream, scores, p.L, p.l_p,
-                         w.n_sort, p.idx_out, reinterpret_cast<uint64_t*>(ws + w.sort_keys_off),
-                         reinterpret_cast<uint32_t*>(ws + w.sort_idx_off), p.hkv);
+      launch(select_kernel<true>, dim3(p.hkv, p.batch), dim3(kSelectThreads), 0, scores, p.L, p.l_p, w.n_sort, p.idx_out, reinterpret_cast<uint64_t*>(ws + w.sort_keys_off), reinterpret_cast<uint32_t*>(ws + w.sort_idx_off), p.hkv);
     } else {
-      int device = 0;
-      (void)hipGetDevice(&device);
-      std::call_once(g_attr_once[device & (kMaxDevices - 1)], [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<false>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsSortMax * 14));
-      });
       const size_t dyn = (size_t)w.n_sort * 14;
-      hipLaunchKernelGGL(select_kernel<false>, dim3(p.hkv, p.batch), dim3(kSelectThreads), dyn, stream, scores, p.L, p.l_p,
-                         w.n_sort, p.idx_out, nullptr, nullptr, p.hkv);
+      launch(select_kernel<false>, dim3(p.hkv, p.batch), dim3(kSelectThreads), dyn, scores, p.L, p.l_p, w.n_sort, p.idx_out, nullptr, nullptr, p.hkv);
     }
     // gather
     const int64_t n_items = p.l_p * p.hkv * (p.d / 8);
     dim3 grid((unsigned)((n_items + 255) / 256), p.batch);
     if (p.d == 128)
-      hipLaunchKernelGGL(gather_kernel<128>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.L, p.k_c, p.v_c);
+      launch(gather_kernel<128>, grid, dim3(256), 0, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.L, p.k_c, p.v_c);
     else
-      hipLaunchKernelGGL(gather_kernel<64>, grid, dim3(256), 0, stream, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.L, p.k_c, p.v_c);
+      launch(gather_kernel<64>, grid, dim3(256), 0, p.k, p.v, p.idx_out, p.l_p, p.hkv, p.L, p.k_c, p.v_c);
   }
-  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+  return launch.status();
 }
 
 }  // namespace apbv

@@ -77,13 +77,14 @@ static apbv_status launch_merge_variant(const MergeParams& p, hipStream_t stream
   const int64_t threads = (int64_t)p.batch * p.rows * p.hq * (p.d / 8) * LP;
   const int64_t blocks = (threads + 255) / 256;
   if (blocks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
+  Launcher launch(stream);
   if (p.d == 128)
-    hipLaunchKernelGGL((merge_lse_kernel<128, LP>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    launch(merge_lse_kernel<128, LP>, dim3((unsigned)blocks), dim3(256), 0, p);
   else if (p.d == 64)
-    hipLaunchKernelGGL((merge_lse_kernel<64, LP>), dim3((unsigned)blocks), dim3(256), 0, stream, p);
+    launch(merge_lse_kernel<64, LP>, dim3((unsigned)blocks), dim3(256), 0, p);
   else
     return APBV_ERR_UNSUPPORTED;
-  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+  return launch.status();
 }
 
 apbv_status launch_merge_lse(const MergeParams& p, hipStream_t stream) {

@@ -362,7 +362,6 @@ __global__ __launch_bounds__(256) void row_stats_combine_kernel(const RowsParams
   if (lane == 0) p.stats[w] = cr;
 }
 
-size_t align256(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
 
@@ -373,9 +372,24 @@ size_t matrix_scores_workspace_bytes(int reducer, int batch, int hkv, int64_t n_
   return align256((size_t)batch * hkv * n_chunks * r_pad * sizeof(float2)) + align256((size_t)batch * hkv * r_pad * sizeof(float));
 }
 
-apbv_status launch_matrix_scores(const CompressParams& cp, double* scores, void* stats_ws, hipStream_t stream) {
+// Shapes the matrix reductions do not implement, reported before anything is launched.
+apbv_status check_matrix_scores(const CompressParams& cp) {
   const int64_t n_rows = cp.q_probe.tokens * cp.group;
   if (n_rows > (1 << 24)) return APBV_ERR_UNSUPPORTED;
+  if (cp.reducer == APBV_REDUCE_SOFTMAX_SUM) {
+    if ((n_rows + 31) / 32 * 32 > kMaxStatRows) return APBV_ERR_UNSUPPORTED;
+    const int64_t n_chunks = (cp.L + kChunkKeys - 1) / kChunkKeys;
+    if (((n_rows + 31) / 32 * 32 + kResident - 1) / kResident * n_chunks > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
+  } else if (cp.reducer != APBV_REDUCE_MAX) {
+    return APBV_ERR_UNSUPPORTED;
+  }
+  return APBV_OK;
+}
+
+apbv_status launch_matrix_scores(const CompressParams& cp, double* scores, void* stats_ws, hipStream_t stream) {
+  const apbv_status ok = check_matrix_scores(cp);
+  if (ok != APBV_OK) return ok;
+  const int64_t n_rows = cp.q_probe.tokens * cp.group;
   RowsParams p;
   p.q = cp.q_probe;
   p.k = cp.k;
@@ -391,11 +405,12 @@ apbv_status launch_matrix_scores(const CompressParams& cp, double* scores, void*
   p.s_ws = scores;
   p.s_out = cp.scores_out;
   const dim3 grid((unsigned)((cp.L + kResident - 1) / kResident), cp.hkv, cp.batch);
+  Launcher launch(stream);
   if (cp.reducer == APBV_REDUCE_MAX) {
     if (cp.d == 128)
-      hipLaunchKernelGGL((matrix_reduce_kernel<128, kMax>), grid, dim3(256), 0, stream, p);
+      launch(matrix_reduce_kernel<128, kMax>, grid, dim3(256), 0, p);
     else
-      hipLaunchKernelGGL((matrix_reduce_kernel<64, kMax>), grid, dim3(256), 0, stream, p);
+      launch(matrix_reduce_kernel<64, kMax>, grid, dim3(256), 0, p);
   } else if (cp.reducer == APBV_REDUCE_SOFTMAX_SUM) {
     if (p.r_pad > kMaxStatRows) return APBV_ERR_UNSUPPORTED;
     p.partial = static_cast<float2*>(stats_ws);
@@ -405,20 +420,20 @@ apbv_status launch_matrix_scores(const CompressParams& cp, double* scores, void*
     if (n_wg > 0x7fffffff) return APBV_ERR_UNSUPPORTED;
     const dim3 sgrid((unsigned)n_wg, cp.hkv, cp.batch);
     if (cp.d == 128)
-      hipLaunchKernelGGL((matrix_reduce_kernel<128, kStats>), sgrid, dim3(256), 0, stream, p);
+      launch(matrix_reduce_kernel<128, kStats>, sgrid, dim3(256), 0, p);
     else
-      hipLaunchKernelGGL((matrix_reduce_kernel<64, kStats>), sgrid, dim3(256), 0, stream, p);
+      launch(matrix_reduce_kernel<64, kStats>, sgrid, dim3(256), 0, p);
     const int64_t n_stat = (int64_t)cp.batch * cp.hkv * p.r_pad;
-    hipLaunchKernelGGL(row_stats_combine_kernel, dim3((unsigned)((n_stat + 3) / 4)), dim3(256), 0, stream, p, cp.batch);
+    launch(row_stats_combine_kernel, dim3((unsigned)((n_stat + 3) / 4)), dim3(256), 0, p, cp.batch);
     const size_t lds = (size_t)p.r_pad * sizeof(float);
     if (cp.d == 128)
-      hipLaunchKernelGGL((matrix_reduce_kernel<128, kMass>), grid, dim3(256), lds, stream, p);
+      launch(matrix_reduce_kernel<128, kMass>, grid, dim3(256), lds, p);
     else
-      hipLaunchKernelGGL((matrix_reduce_kernel<64, kMass>), grid, dim3(256), lds, stream, p);
+      launch(matrix_reduce_kernel<64, kMass>, grid, dim3(256), lds, p);
   } else {
     return APBV_ERR_UNSUPPORTED;
   }
-  return hipGetLastError() == hipSuccess ? APBV_OK : APBV_ERR_LAUNCH;
+  return launch.status();
 }
 
 }  // namespace apbv

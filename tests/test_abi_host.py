@@ -191,12 +191,31 @@ def test_product_path_has_no_oracle_or_cpu_fallback():
         b._lib, b._LIB_PATH = saved_lib, saved_path
 
 
-def test_group_schedule_covers_every_query_tile_once(tmp_path):
-    """The merged heaviest-first schedule of apbv_host_attention_group, checked by brute force on the host."""
+SANITIZE = ["-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-g",
+            "-static-libasan", "-static-libubsan"]       # static runtimes: independent of the process's preload list
+
+
+def build_and_run_host_check(tmp_path, name):
+    """Compile tests/host/<name>.cpp with the host compiler under the address and undefined-behaviour sanitizers
+    (no HIP involved: the headers it includes are plain C++) and run it."""
     import subprocess
-    exe = tmp_path / "schedule_check"
-    src = os.path.join(ROOT, "tests", "host", "schedule_check.cpp")
-    inc = os.path.join(ROOT, "paper_2601_21444_amd", "csrc")
-    subprocess.run(["g++", "-O1", "-std=c++17", "-Wall", "-I", inc, src, "-o", str(exe)], check=True)
-    res = subprocess.run([str(exe)], capture_output=True, text=True)
+    exe = tmp_path / name
+    src = os.path.join(ROOT, "tests", "host", name + ".cpp")
+    incs = ["-I", os.path.join(ROOT, "paper_2601_21444_amd", "csrc"), "-I", os.path.join(ROOT, "include")]
+    subprocess.run(["g++", "-O1", "-std=c++17", "-Wall", *SANITIZE, *incs, src, "-o", str(exe)], check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    return subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+
+
+def test_group_schedule_covers_every_query_tile_once(tmp_path):
+    """The merged heaviest-first schedule of apbv_host_attention_group, checked by brute force on the host, under
+    the sanitizers."""
+    res = build_and_run_host_check(tmp_path, "schedule_check")
     assert res.returncode == 0 and "schedule ok" in res.stdout, res.stdout + res.stderr
+
+
+def test_host_validation_under_sanitizers(tmp_path):
+    """Every rejection case of the C ABI's host-side validation and the workspace / key-split planners, compiled
+    alone with g++ -fsanitize=address,undefined."""
+    res = build_and_run_host_check(tmp_path, "validation_check")
+    assert res.returncode == 0 and "host validation OK" in res.stdout, res.stdout + res.stderr
