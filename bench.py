@@ -30,12 +30,25 @@ if ROOT not in sys.path:
 PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBPS = 8000.0           # MI355X HBM3E, published
 
-# HBM traffic per launch of the dominant kernel (bytes), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# each scaled by the same counter's reading for a copy kernel of known size; see profiles/.  None until
-# measured.
-MEASURED_TRAFFIC_BYTES = 446905394   # profiles/host_attention_3b-128k_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, KiB)
-# the same for one batch-96 compression call (its four kernels together); profiles/compress_3b-128k_batch96_pmc.txt
-MEASURED_COMPRESS_TRAFFIC_BYTES = 1088141755
+
+
+def measured_traffic(rel: str, library_version: int):
+    """HBM traffic per launch (bytes) as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by the same
+    counter's reading for a copy of known size).  The figure is not measured by this run: it is read from the committed
+    summary `rel` (profiles/..._<workload>_pmc.txt), which ends with a line
+        TRAFFIC_BYTES_PER_LAUNCH <bytes> library_version <v>
+    and is reported only for the workload it was measured on and only while the library still has the version it
+    was measured with; otherwise (None, None).  Returns (bytes, path relative to the repository)."""
+    try:
+        with open(os.path.join(ROOT, rel)) as f:
+            lines = [ln.split() for ln in f if ln.startswith("TRAFFIC_BYTES_PER_LAUNCH")]
+    except OSError:
+        return None, None
+    for w in lines:
+        if len(w) >= 4 and w[2] == "library_version" and int(w[3]) == library_version:
+            return int(w[1]), rel
+    return None, None
+
 
 
 def parse_args():
@@ -51,6 +64,7 @@ def parse_args():
                     help="also run one plain 1 GiB device copy (reference dispatch for scaling rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--no-extras", action="store_true", help="skip the short timings of the query-block, physical-host "
                     "and alternative-reduction entry points")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the short timings of the other configurations")
     ap.add_argument("--compress-batch", type=int, default=96,
                     help="batch of the HBM-bound compression measurement (working set far beyond the 256 MB cache)")
     return ap.parse_args()
@@ -163,8 +177,11 @@ def main():
                             "gbps": round(cfg.compress_bytes / (comp_avg_ms * 1e-3) / 1e9, 2)},
         "roofline": {"bound": "mfma", "kernel": "host_attention_kernel", "achieved": round(attn_tflops, 2),
                      "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_MFMA_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES},
+                     "traffic": None, "traffic_source": None},
     }
+    result["roofline"]["traffic"], result["roofline"]["traffic_source"] = measured_traffic(
+        f"profiles/host_attention_{name}_pmc.txt", apbv.apbv_version())
+
 
     # the two virtual hosts of a physical host as one batched call (Sec. 4.3)
     k2, v2, qp2 = (t.unsqueeze(0).repeat(2, 1, 1, 1) for t in (k, v, q_probe))
@@ -187,6 +204,11 @@ def main():
         del src, dst
     if not args.no_compress_roofline:
         result["roofline_compress"] = compress_roofline(apbv, torch, cfg, q_probe, k, v, args.compress_batch)
+        rc = result["roofline_compress"]
+        rc["traffic"], rc["traffic_source"] = measured_traffic(
+            f"profiles/compress_{name}_batch{args.compress_batch}_pmc.txt", apbv.apbv_version())
+    if not args.no_per_config:
+        result["per_config"] = per_config(apbv, torch, np, wl, name, result)
     if not args.no_extras:
         result["extras"] = extras(apbv, torch, cfg, q_probe, q, k_a, v_a, k_p, v_p, k, v, scale)
     if not args.no_cpu_baseline:
@@ -206,6 +228,46 @@ def timed(torch, fn, iters=10, warmup=3):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def per_config(apbv, torch, np, wl, headline, headline_result):
+    """Every configuration of workloads.CONFIGS through the two calls of the hot path, a few launches each (context
+    beside the headline fields; the headline's own entry repeats the figures of the timed steps)."""
+    out = {}
+    for name, cfg in wl.CONFIGS.items():
+        if name == headline:
+            a, c = headline_result["attention"], headline_result["compress_batch1"]
+            out[name] = {"attention_ms": a["ms_avg"], "tflops": a["tflops"], "frac_bf16_mfma_peak": round(a["tflops"] / PEAK_BF16_MFMA_TFLOPS, 4),
+                         "compress_us": c["us_avg"]}
+            continue
+        x = wl.generate(cfg)
+
+        def dev(bits):
+            return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).view(torch.bfloat16).cuda()
+        q_probe, q, k_a, v_a, k, v = (dev(a) for a in (x.q_probe, x.q, x.k_anchor, x.v_anchor, x.k, x.v))
+        kps, vps = [], []
+        for kb, vb in zip(x.k_prev, x.v_prev):
+            _, a, b = apbv.apbv_compress_kv(q_probe, dev(kb), dev(vb), cfg.l_p)
+            kps.append(a)
+            vps.append(b)
+        empty = torch.empty((0, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+        k_p = torch.cat(kps) if kps else empty
+        v_p = torch.cat(vps) if vps else empty
+        ws = torch.empty(max(apbv.apbv_compress_workspace_bytes(1, cfg.n_kv_heads, cfg.head_dim, cfg.L, cfg.l_p), 256),
+                         dtype=torch.uint8, device="cuda")
+        idx = torch.empty((1, cfg.n_kv_heads, cfg.l_p), dtype=torch.int32, device="cuda")
+        k_c = torch.empty((1, cfg.l_p, cfg.n_kv_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+        v_c = torch.empty_like(k_c)
+        o = torch.empty((1, cfg.L, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device="cuda")
+        scale = 1.0 / math.sqrt(cfg.head_dim)
+        ms_a = timed(torch, lambda: apbv.apbv_host_attention(q, k_a, v_a, k_p, v_p, k, v, scale, out=o), iters=8, warmup=2)
+        ms_c = timed(torch, lambda: apbv.apbv_compress_kv(q_probe, k, v, cfg.l_p, workspace=ws, idx_out=idx, k_c_out=k_c,
+                                                          v_c_out=v_c), iters=20, warmup=3)
+        tf = cfg.attention_flops / (ms_a * 1e-3) / 1e12
+        out[name] = {"attention_ms": round(ms_a, 4), "tflops": round(tf, 2),
+                     "frac_bf16_mfma_peak": round(tf / PEAK_BF16_MFMA_TFLOPS, 4), "compress_us": round(ms_c * 1e3, 2)}
+        del x, q_probe, q, k_a, v_a, k, v, k_p, v_p, kps, vps, o
+    return out
 
 
 def extras(apbv, torch, cfg, q_probe, q, k_a, v_a, k_p, v_p, k, v, scale):
@@ -311,7 +373,6 @@ def compress_roofline(apbv, torch, cfg, q_probe, k, v, batch):
     return {"bound": "hbm", "kernel": "pool+score+select+gather", "batch": batch, "achieved": round(gbps, 1),
             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(gbps / PEAK_HBM_GBPS, 4),
             "ms_per_call": round(ms, 4), "algorithmic_bytes_per_call": nbytes,
-            "traffic": MEASURED_COMPRESS_TRAFFIC_BYTES if batch == 96 else None,
             "score_pass": {"kernel": "pool+score (l_p = 0)", "achieved": round(gbps_score, 1), "unit": "GB/s",
                            "frac": round(gbps_score / PEAK_HBM_GBPS, 4), "ms_per_call": round(ms_score, 4),
                            "algorithmic_bytes_per_call": k_bytes}}
