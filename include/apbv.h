@@ -18,8 +18,8 @@
  *     parameter is explicitly marked host.  bf16 values are passed as their 16-bit patterns.
  *   - The caller owns every buffer (inputs, outputs, workspace).  The library allocates no device
  *     memory.  Its only state is a per-device one-time set-up made by the first compression call on a device
- *     (apbv_compress_kv, apbv_compress_kv_reduced): a function attribute of the selection kernel.  No results
- *     depend on it.
+ *     (apbv_compress_kv, apbv_compress_kv_reduced, apbv_compress_kv_noalloc): a function attribute of the selection
+ *     kernel and the device address of the static scratch array of apbv_compress_kv_noalloc.  No results depend on it.
  *   - Calls are asynchronous: work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and outputs are valid once the caller has synchronised that stream.  The calls can be
  *     captured into a HIP graph (they enqueue kernels only); make the first compression call on a device before
@@ -99,6 +99,26 @@ apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_
                              int64_t l_p,
                              int32_t* idx_out, void* k_c_out, void* v_c_out, double* scores_out,
                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * apbv_compress_kv for callers that cannot allocate or hand over a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same operation, arguments, outputs and results as
+ * apbv_compress_kv (bit-identical), without the workspace arguments: the intermediate pooled query and scores live in
+ * a static device array of APBV_NOALLOC_MAX_WORKSPACE_BYTES bytes inside the library, one copy per GPU, held until
+ * the process ends.  The call allocates nothing and frees nothing.
+ *
+ * Limits: apbv_compress_workspace_bytes(batch, n_kv_heads, head_dim, L, l_p) must not exceed
+ * APBV_NOALLOC_MAX_WORKSPACE_BYTES (about batch * n_kv_heads * L <= 500 000 scores), else APBV_ERR_WORKSPACE and
+ * nothing is launched.  All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams or host threads without ordering between them) race and give unspecified results; calls ordered on one
+ * stream, or by events, are fine.  The array's previous contents are never read before they are rewritten.
+ */
+#define APBV_NOALLOC_MAX_WORKSPACE_BYTES 4194304
+apbv_status apbv_compress_kv_noalloc(int batch, int n_q_heads, int n_kv_heads, int head_dim,
+                                     apbv_tensor q_probe, apbv_tensor k_local, apbv_tensor v_local,
+                                     int64_t l_p,
+                                     int32_t* idx_out, void* k_c_out, void* v_c_out, double* scores_out,
+                                     void* hip_stream);
 
 /*
  * How the n_q*G x L score matrix S_h = Q_qr K^(h)T of Alg. 1 becomes one score per key and KV head (the paper does

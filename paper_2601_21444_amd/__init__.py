@@ -9,6 +9,8 @@ from .binding import (  # noqa: F401
     ApbvAttentionItem,
     ApbvTensor,
     apbv_compress_kv,
+    apbv_compress_kv_noalloc,
+    NOALLOC_MAX_WORKSPACE_BYTES,
     apbv_compress_reduced_workspace_bytes,
     apbv_compress_workspace_bytes,
     apbv_host_attention,

@@ -67,6 +67,8 @@ def load_library() -> ctypes.CDLL:
         ApbvTensor, ApbvTensor, ApbvTensor, ctypes.c_int64,
         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    lib.apbv_compress_kv_noalloc.restype = ctypes.c_int
+    lib.apbv_compress_kv_noalloc.argtypes = list(lib.apbv_compress_kv.argtypes[:12]) + [ctypes.c_void_p]
     lib.apbv_compress_reduced_workspace_bytes.restype = ctypes.c_size_t
     lib.apbv_compress_reduced_workspace_bytes.argtypes = [
         ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64]
@@ -207,6 +209,37 @@ def apbv_compress_kv(q_probe: torch.Tensor, k_local: torch.Tensor, v_local: torc
         scores_out = scores_out[0] if scores_out is not None else None
     if return_scores:
         return idx_out, k_c_out, v_c_out, scores_out
+    return idx_out, k_c_out, v_c_out
+
+
+NOALLOC_MAX_WORKSPACE_BYTES = 4194304      # APBV_NOALLOC_MAX_WORKSPACE_BYTES of include/apbv.h
+
+
+def apbv_compress_kv_noalloc(q_probe: torch.Tensor, k_local: torch.Tensor, v_local: torch.Tensor, l_p: int, *,
+                             idx_out: torch.Tensor, k_c_out: torch.Tensor, v_c_out: torch.Tensor,
+                             scores_out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None):
+    """apbv_compress_kv without a workspace (the library's static scratch array) and without any allocation here
+    either: the caller passes every output.  See apbv_compress_kv_noalloc in include/apbv.h."""
+    lib = load_library()
+    qv, bq = tensor_view(q_probe)
+    kv, b = tensor_view(k_local)
+    vv, bv = tensor_view(v_local)
+    if not (bq == b == bv):
+        raise ValueError("batch sizes differ")
+    hq, d = q_probe.shape[-2], q_probe.shape[-1]
+    hkv, L = k_local.shape[-2], k_local.shape[-3]
+    dev = k_local.device
+    _check_buffer(idx_out, "idx_out", torch.int32, (b, hkv, l_p), dev)
+    _check_buffer(k_c_out, "k_c_out", torch.bfloat16, (b, l_p, hkv, d), dev)
+    _check_buffer(v_c_out, "v_c_out", torch.bfloat16, (b, l_p, hkv, d), dev)
+    _check_buffer(scores_out, "scores_out", torch.float64, (b, hkv, L), dev)
+    st = lib.apbv_compress_kv_noalloc(
+        b, hq, hkv, d, qv, kv, vv, int(l_p),
+        idx_out.data_ptr() if l_p > 0 else None, k_c_out.data_ptr() if l_p > 0 else None,
+        v_c_out.data_ptr() if l_p > 0 else None,
+        scores_out.data_ptr() if scores_out is not None else None, _stream_ptr(stream))
+    if st != 0:
+        raise ApbvError(st, "apbv_compress_kv_noalloc")
     return idx_out, k_c_out, v_c_out
 
 

@@ -122,7 +122,9 @@ struct CompressParams {
   size_t workspace_bytes;
   int reducer;            // apbv_reducer: how the score matrix becomes one score per key
   float scale_log2;       // softmax_scale * log2(e), for APBV_REDUCE_SOFTMAX_SUM
+  bool use_static_scratch;   // workspace = the library's static device array (workspace / workspace_bytes ignored)
 };
+constexpr size_t kStaticScratchBytes = APBV_NOALLOC_MAX_WORKSPACE_BYTES;   // size of that array
 
 // workspace = [selection workspace | row statistics of the matrix reductions]
 size_t compress_workspace_bytes(int batch, int hkv, int d, int64_t L, int64_t l_p);

@@ -49,13 +49,17 @@ size_t reduced_workspace_bytes(int reducer, int batch, int hq, int hkv, int d, i
 apbv_status compress_entry(int reducer, float softmax_scale, int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_probe,
                              apbv_tensor k_local, apbv_tensor v_local, int64_t l_p, int32_t* idx_out, void* k_c_out,
                              void* v_c_out, double* scores_out, void* workspace, size_t workspace_bytes,
-                             void* hip_stream) {
+                             void* hip_stream, bool use_static_scratch = false) {
   const apbv_status st = validate_compress(reducer, softmax_scale, batch, n_q_heads, n_kv_heads, head_dim, q_probe, k_local,
                                            v_local, l_p, idx_out, k_c_out, v_c_out, scores_out);
   if (st != APBV_OK) return st;
   const int64_t L = k_local.tokens;
   const size_t need = reduced_workspace_bytes(reducer, batch, n_q_heads, n_kv_heads, head_dim, q_probe.tokens, L, l_p);
-  if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) return APBV_ERR_WORKSPACE;
+  if (use_static_scratch) {
+    if (need > kStaticScratchBytes) return APBV_ERR_WORKSPACE;      // beyond the static array: use apbv_compress_kv
+  } else if (workspace == nullptr || !aligned(workspace, 256) || workspace_bytes < need) {
+    return APBV_ERR_WORKSPACE;
+  }
 
   CompressParams p;
   p.q_probe = to_view(q_probe);
@@ -76,6 +80,7 @@ apbv_status compress_entry(int reducer, float softmax_scale, int batch, int n_q_
   p.workspace_bytes = workspace_bytes;
   p.reducer = reducer;
   p.scale_log2 = softmax_scale * 1.4426950408889634f;
+  p.use_static_scratch = use_static_scratch;
   return launch_compress(p, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -90,7 +95,7 @@ const char* apbv_status_string(apbv_status s) {
     case APBV_ERR_NULL: return "APBV_ERR_NULL: a required pointer is NULL";
     case APBV_ERR_SHAPE: return "APBV_ERR_SHAPE: inconsistent or out-of-range sizes or strides";
     case APBV_ERR_UNSUPPORTED: return "APBV_ERR_UNSUPPORTED: head_dim or size not implemented";
-    case APBV_ERR_WORKSPACE: return "APBV_ERR_WORKSPACE: workspace NULL, misaligned or too small";
+    case APBV_ERR_WORKSPACE: return "APBV_ERR_WORKSPACE: workspace NULL, misaligned or too small (or, without a workspace argument, the shape needs more than the static scratch array holds)";
     case APBV_ERR_LAUNCH: return "APBV_ERR_LAUNCH: the HIP runtime refused a kernel launch";
   }
   return "unknown apbv_status";
@@ -108,6 +113,13 @@ apbv_status apbv_compress_kv(int batch, int n_q_heads, int n_kv_heads, int head_
                              void* hip_stream) {
   return compress_entry(APBV_REDUCE_SUM, 0.0f, batch, n_q_heads, n_kv_heads, head_dim, q_probe, k_local, v_local, l_p,
                         idx_out, k_c_out, v_c_out, scores_out, workspace, workspace_bytes, hip_stream);
+}
+
+apbv_status apbv_compress_kv_noalloc(int batch, int n_q_heads, int n_kv_heads, int head_dim, apbv_tensor q_probe,
+                                     apbv_tensor k_local, apbv_tensor v_local, int64_t l_p, int32_t* idx_out,
+                                     void* k_c_out, void* v_c_out, double* scores_out, void* hip_stream) {
+  return compress_entry(APBV_REDUCE_SUM, 0.0f, batch, n_q_heads, n_kv_heads, head_dim, q_probe, k_local, v_local, l_p,
+                        idx_out, k_c_out, v_c_out, scores_out, nullptr, 0, hip_stream, true);
 }
 
 size_t apbv_compress_reduced_workspace_bytes(int reducer, int batch, int n_q_heads, int n_kv_heads, int head_dim,

@@ -526,11 +526,17 @@ __global__ __launch_bounds__(256) void gather_kernel(View k, View v, const int32
   __builtin_nontemporal_store(vv, reinterpret_cast<u32x4*>(v_c + dst));
 }
 
+// Scratch of the entry point that takes no workspace (apbv_compress_kv_noalloc): a fixed array in the code object,
+// one copy per GPU at that GPU's own address.  In host code the array's name is only a handle for the symbol lookup
+// below; kernels and launch code use the looked-up device address.
+__device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 // Per-device one-time set-up (the library's only state): the selection kernel's dynamic-LDS limit, which is a
-// per-device property of the loaded code object.
+// per-device property of the loaded code object, and the device address of `scratch`.
 constexpr int kMaxDevices = 64;
 struct DeviceState {
   bool ready = false;
+  void* scratch_ptr = nullptr;
 };
 std::mutex g_state_mutex;
 DeviceState g_state[kMaxDevices];
@@ -545,6 +551,9 @@ apbv_status device_state(DeviceState& out) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
                             (int)(kLdsSortMax * 14)) != hipSuccess)
       return APBV_ERR_LAUNCH;
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return APBV_ERR_LAUNCH;
+    st.scratch_ptr = ptr;
     st.ready = true;
   }
   out = st;
@@ -567,6 +576,12 @@ apbv_status launch_compress(const CompressParams& p_in, hipStream_t stream) {
   DeviceState dev;
   const apbv_status ds = device_state(dev);
   if (ds != APBV_OK) return ds;
+  if (p.use_static_scratch) {
+    // the workspace is this GPU's copy of the static array: every such call on the GPU shares it
+    if (p.reducer != APBV_REDUCE_SUM || w.total > kStaticScratchBytes) return APBV_ERR_WORKSPACE;
+    p.workspace = dev.scratch_ptr;
+    p.workspace_bytes = kStaticScratchBytes;
+  }
   if (p.workspace_bytes < w.total) return APBV_ERR_WORKSPACE;
   unsigned char* ws = static_cast<unsigned char*>(p.workspace);
   double* qbar = reinterpret_cast<double*>(ws + w.qbar_off);

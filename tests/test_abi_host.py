@@ -21,7 +21,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = apbv.load_library()
     names = declared_symbols()
-    assert names == ["apbv_compress_kv", "apbv_compress_kv_reduced", "apbv_compress_reduced_workspace_bytes",
+    assert names == ["apbv_compress_kv", "apbv_compress_kv_noalloc", "apbv_compress_kv_reduced", "apbv_compress_reduced_workspace_bytes",
                      "apbv_compress_workspace_bytes", "apbv_host_attention", "apbv_host_attention_group",
                      "apbv_merge_lse",
                      "apbv_query_attention", "apbv_query_attention_workspace_bytes", "apbv_status_string",
@@ -95,6 +95,20 @@ def test_compress_rejects_bad_arguments_without_launching():
     assert call_compress(n_q=0) == -2
     assert call_compress(v=view(63, 2, 128)) == -2
     assert call_compress(kc=0x4002) == -2
+
+
+def test_compress_noalloc_rejects_bad_arguments_and_oversize_without_launching():
+    lib = apbv.load_library()
+
+    def call(batch=1, hq=4, hkv=2, d=128, n_q=4, L=64, l_p=8, idx=0x3000, kc=0x4000, vc=0x5000):
+        return lib.apbv_compress_kv_noalloc(batch, hq, hkv, d, view(n_q, hq, d), view(L, hkv, d), view(L, hkv, d), l_p,
+                                            idx, kc, vc, None, None)
+    assert call(l_p=65) == -2 and call(hq=5) == -2 and call(d=32) == -3 and call(idx=None) == -1
+    # a shape whose workspace exceeds the static array is refused with the workspace status
+    assert apbv.apbv_compress_workspace_bytes(64, 2, 128, 16384, 8) > apbv.NOALLOC_MAX_WORKSPACE_BYTES
+    assert call(batch=64, L=16384) == -4
+    assert apbv.apbv_compress_workspace_bytes(2, 4, 128, 16384, 2048) <= apbv.NOALLOC_MAX_WORKSPACE_BYTES
+    assert b"static scratch" in lib.apbv_status_string(-4)
 
 
 def test_compress_reduced_rejects_bad_arguments_without_launching():
