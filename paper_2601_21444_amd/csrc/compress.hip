@@ -41,24 +41,29 @@ __device__ __forceinline__ double dpp_f64(double x) {
 
 // ------------------------------------------------------------------------------------------------
 // q_bar[b, v, c] = sum_g sum_t Q_qr[b, t, v*G+g, c]   (float64; the addends are bf16 so the sum is
-// exact or within an ulp whatever the order).  One workgroup per (KV head, batch item): D/8 lanes per
-// probe row (16-byte loads), 1024/(D/8) rows in flight, then a shuffle + LDS reduction.
-template <int D>
-__global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, int group, double* qbar, int hkv) {
+// exact or within an ulp whatever the order).  The n_q * G probe rows of a (KV head, batch item) are
+// cut into n_split equal ranges, one workgroup each (so that even a single item spreads over several
+// compute units); a workgroup writes the partial sum of its range and the scoring kernel adds the
+// partial sums in index order.  D/8 lanes per probe row (16-byte loads), T/(D/8) rows in flight (T = 1024 threads
+// where a range is long enough to feed them four loads each, 256 otherwise).
+template <int D, int T>
+__global__ __launch_bounds__(T) void pool_query_kernel(View q, int64_t n_q, int group, double* qpart, int hkv, int n_split) {
   constexpr int KC = D / 8;
-  constexpr int R = 1024 / KC;                 // row groups
-  __shared__ double part[16][D];
-  const int v = blockIdx.x, b = blockIdx.y;
+  constexpr int R = T / KC;                    // row groups
+  __shared__ double part[T / 64][D];
+  const int sp = blockIdx.x, v = blockIdx.y, b = blockIdx.z;
   const int c8 = threadIdx.x % KC, rg = threadIdx.x / KC;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const bf16_t* base = q.ptr + (int64_t)b * q.sb + (int64_t)v * group * q.sh + 8 * c8;
   double acc[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) acc[e] = 0.0;
-  // rows (t, g) in steps of R, four loads in flight; (t, g) advance without divisions in the loop
   const int n_rows = (int)(n_q * group);
+  const int per = (n_rows + n_split - 1) / n_split;
+  const int r_begin = sp * per, r_end = r_begin + per < n_rows ? r_begin + per : n_rows;
+  // rows (t, g) in steps of R, four loads in flight; (t, g) advance without divisions in the loop
   const int dt = R / group, dg = R % group;
-  int t = rg / group, g = rg % group;
+  int t = (r_begin + rg) / group, g = (r_begin + rg) % group;
   auto advance = [&]() {
     t += dt;
     g += dg;
@@ -67,12 +72,12 @@ __global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, i
       ++t;
     }
   };
-  for (int rr = rg; rr < n_rows; rr += 4 * R) {
+  for (int rr = r_begin + rg; rr < r_end; rr += 4 * R) {
     u32x4 x[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       x[u] = u32x4{0u, 0u, 0u, 0u};                       // +0.0: adds nothing
-      if (rr + u * R < n_rows) x[u] = *reinterpret_cast<const u32x4*>(base + (int64_t)t * q.st + (int64_t)g * q.sh);
+      if (rr + u * R < r_end) x[u] = *reinterpret_cast<const u32x4*>(base + (int64_t)t * q.st + (int64_t)g * q.sh);
       advance();
     }
 #pragma unroll
@@ -96,8 +101,8 @@ __global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, i
   if (threadIdx.x < D) {
     double sum = 0.0;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) sum += part[w][threadIdx.x];
-    qbar[((int64_t)b * hkv + v) * D + threadIdx.x] = sum;
+    for (int w = 0; w < T / 64; ++w) sum += part[w][threadIdx.x];
+    qpart[(((int64_t)b * hkv + v) * n_split + sp) * D + threadIdx.x] = sum;
   }
 }
 
@@ -105,7 +110,7 @@ __global__ __launch_bounds__(1024) void pool_query_kernel(View q, int64_t n_q, i
 // s[b, v, j] = q_bar[b, v, :] . K[b, j, v, :].  D/8 lanes per key row, each lane 8 elements (one
 // 16-byte load), fixed summation order per row so identical rows get identical scores.
 template <int D>
-__global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const double* __restrict__ qbar,
+__global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const double* __restrict__ qpart, int n_split,
                                                     double* __restrict__ s_ws, double* __restrict__ s_out,
                                                     int hkv, int rows_per_block) {
   constexpr int LPR = D / 8;               // lanes per row
@@ -116,7 +121,7 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
   const int c = threadIdx.x % LPR;
   const int rsub = threadIdx.x / LPR;
   __shared__ double qs[D];
-  const double* qb = qbar + ((int64_t)b * hkv + v) * D;
+  const double* qb = qpart + ((int64_t)b * hkv + v) * n_split * D;      // n_split partial sums of the pooled query
   const bf16_t* base = k.ptr + (int64_t)b * k.sb + (int64_t)v * k.sh + 8 * c;
   const int64_t out_base = ((int64_t)b * hkv + v) * L;
   const int64_t r_begin = (int64_t)blockIdx.x * rows_per_block;
@@ -135,7 +140,20 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
     // key loads, instead of four loads per lane in front of them.
     if (r0 == r_begin) {
       if (threadIdx.x < D / 2) {
-        const double2 t = *reinterpret_cast<const double2*>(qb + 2 * threadIdx.x);
+        // all partial sums are fetched before the first addition (independent loads), then added in index order
+        double2 part[kPoolSplitMax];
+#pragma unroll
+        for (int sp = 0; sp < kPoolSplitMax; ++sp) {
+          part[sp] = double2{0.0, 0.0};
+          if (sp < n_split) part[sp] = *reinterpret_cast<const double2*>(qb + sp * D + 2 * threadIdx.x);
+        }
+        double2 t = part[0];
+#pragma unroll
+        for (int sp = 1; sp < kPoolSplitMax; ++sp)
+          if (sp < n_split) {
+            t.x += part[sp].x;
+            t.y += part[sp].y;
+          }
         qs[2 * threadIdx.x] = t.x;
         qs[2 * threadIdx.x + 1] = t.y;
       }
@@ -197,22 +215,60 @@ struct SelectShared {
   uint32_t base[kBins];       // entries in higher buckets (output offset of the bucket)
   uint32_t fill[kBins];       // scatter cursor per bucket
   uint64_t prefix;
-  uint32_t need, bucket, cnt, n_cand, t_bin, max_bin;
+  uint32_t need, bucket, cnt, n_cand, t_bin, crowded;
   uint32_t wave_tot[kSelectThreads / 64];
-  double red_lo[kSelectThreads / 64], red_hi[kSelectThreads / 64];
+  float red_lo[kSelectThreads / 64], red_hi[kSelectThreads / 64];
 };
 
+// Wave-wide combinations on the DPP data path (no LDS traffic): shifts inside the 16-lane rows, then lane 15 of
+// a row into the next row and lane 31 into the upper half.  A lane whose source lies outside keeps `self`.
+constexpr int kDppShr1 = 0x111, kDppShr2 = 0x112, kDppShr4 = 0x114, kDppShr8 = 0x118;   // row_shr:n
+constexpr int kDppBcast15 = 0x142, kDppBcast31 = 0x143;
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_self(uint32_t self, uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)self, (int)x, CTRL, ROW_MASK, 0xf, false);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave.
+__device__ __forceinline__ uint32_t wave_scan_incl(uint32_t x) {
+  x += dpp_or_self<kDppShr1, 0xf>(0u, x);
+  x += dpp_or_self<kDppShr2, 0xf>(0u, x);
+  x += dpp_or_self<kDppShr4, 0xf>(0u, x);
+  x += dpp_or_self<kDppShr8, 0xf>(0u, x);
+  x += dpp_or_self<kDppBcast15, 0xa>(0u, x);
+  x += dpp_or_self<kDppBcast31, 0xc>(0u, x);
+  return x;
+}
+
+// op over the 64 lanes of a wave, the result in every lane (lane 63 collects it, one scalar read spreads it).
+template <typename Op>
+__device__ __forceinline__ uint32_t wave_reduce_bits(uint32_t x, Op op) {
+  x = op(x, dpp_or_self<kDppShr1, 0xf>(x, x));
+  x = op(x, dpp_or_self<kDppShr2, 0xf>(x, x));
+  x = op(x, dpp_or_self<kDppShr4, 0xf>(x, x));
+  x = op(x, dpp_or_self<kDppShr8, 0xf>(x, x));
+  x = op(x, dpp_or_self<kDppBcast15, 0xa>(x, x));
+  x = op(x, dpp_or_self<kDppBcast31, 0xc>(x, x));
+  return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+__device__ __forceinline__ float wave_min(float x) {
+  return __uint_as_float(wave_reduce_bits(__float_as_uint(x), [](uint32_t a, uint32_t b) {
+    return __float_as_uint(fminf(__uint_as_float(a), __uint_as_float(b)));
+  }));
+}
+__device__ __forceinline__ float wave_max(float x) {
+  return __uint_as_float(wave_reduce_bits(__float_as_uint(x), [](uint32_t a, uint32_t b) {
+    return __float_as_uint(fmaxf(__uint_as_float(a), __uint_as_float(b)));
+  }));
+}
+
 // Inclusive scan of one value per thread over the whole workgroup (1024 threads); returns the
-// inclusive prefix, *total gets the workgroup sum.
+// inclusive prefix, *total gets the workgroup sum.  kFresh: wave_tot has not been used since the last barrier.
+template <bool kFresh = false>
 __device__ __forceinline__ uint32_t block_scan_incl(uint32_t x, SelectShared& sh, uint32_t* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  uint32_t incl = x;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const uint32_t o = __shfl_up(incl, off);
-    if (lane >= off) incl += o;
-  }
-  __syncthreads();                      // wave_tot may still be read from a previous use
+  const uint32_t incl = wave_scan_incl(x);
+  if (!kFresh) __syncthreads();         // wave_tot may still be read from a previous use
   if (lane == 63) sh.wave_tot[wave] = incl;
   __syncthreads();
   uint32_t base = 0, tot = 0;
@@ -251,14 +307,14 @@ __device__ __forceinline__ void bitonic_sort(uint64_t* skeys, uint32_t* sidx, in
   }
 }
 
-// Fast path: a bucket sort by VALUE.  A monotone map sends every score to one of kBins equal-width
-// buckets between the minimum and the maximum score.  A suffix scan of the bucket counts gives each
-// bucket its output offset and finds the bucket that holds the l_p-th largest score; the entries of
-// that bucket and of all higher ones are scattered into bucket-grouped order, and each entry then finds
-// its rank inside its (small) bucket by direct comparison.  Because the map is monotone, bucket order
-// followed by (key descending, index ascending) inside a bucket is the global order, ties included.
-// Returns false (nothing written) if the candidates do not fit `cap` or a bucket is too crowded to rank
-// by comparison; the caller then takes the exact radix path.
+// Fast path: a bucket sort by VALUE.  A monotone map sends every score to one of kBins buckets of equal width
+// between the minimum and the maximum (computed in single precision: only the order matters).  A suffix scan of
+// the bucket counts gives each bucket its output offset and finds the bucket that holds the l_p-th largest score;
+// the entries of that bucket and of all higher ones are scattered into bucket-grouped order, and each entry then
+// finds its rank inside its (small) bucket by direct comparison of the full 64-bit keys and indices.  Because the
+// map is monotone, bucket order followed by (key descending, index ascending) inside a bucket is the global order,
+// ties included.  Returns false (nothing written) if the candidates do not fit `cap` or a bucket is too crowded to
+// rank by comparison; the caller then takes the exact radix path.
 __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s, int64_t L, int64_t l_p, int64_t cap,
                                                    uint64_t* skeys, uint32_t* sidx, uint16_t* sbin,
                                                    int32_t* __restrict__ idx_out, SelectShared& sh) {
@@ -266,6 +322,7 @@ __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s,
   constexpr int kPer = 16;                                   // scores kept in registers per thread
   const bool resident = L <= (int64_t)kPer * kSelectThreads;
   double sc[kPer];
+  uint32_t bins[kPer];                                       // bucket | arrival order in the bucket << 11
   if (resident) {
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
@@ -273,29 +330,25 @@ __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s,
       sc[u] = j < L ? s[j] : 0.0;
     }
   }
-  // apply f(j, score) to every element this thread owns
-  auto for_each = [&](auto&& f) {
-    if (resident) {
+  // minimum and maximum, in single precision (the conversion is monotone, which is all the map needs)
+  float lo = INFINITY, hi = -INFINITY;
+  if (resident) {
 #pragma unroll
-      for (int u = 0; u < kPer; ++u) {
-        const int64_t j = tid + (int64_t)u * kSelectThreads;
-        if (j < L) f(j, sc[u]);
+    for (int u = 0; u < kPer; ++u)
+      if (tid + (int64_t)u * kSelectThreads < L) {
+        const float x = (float)sc[u];
+        lo = fminf(lo, x);
+        hi = fmaxf(hi, x);
       }
-    } else {
-      for (int64_t j = tid; j < L; j += kSelectThreads) f(j, s[j]);
+  } else {
+    for (int64_t j = tid; j < L; j += kSelectThreads) {
+      const float x = (float)s[j];
+      lo = fminf(lo, x);
+      hi = fmaxf(hi, x);
     }
-  };
-  // minimum and maximum
-  double lo = INFINITY, hi = -INFINITY;
-  for_each([&](int64_t, double x) {
-    lo = fmin(lo, x);
-    hi = fmax(hi, x);
-  });
-#pragma unroll
-  for (int m = 1; m < 64; m <<= 1) {
-    lo = fmin(lo, __shfl_xor(lo, m));
-    hi = fmax(hi, __shfl_xor(hi, m));
   }
+  lo = wave_min(lo);
+  hi = wave_max(hi);
   if (lane == 0) {
     sh.red_lo[wave] = lo;
     sh.red_hi[wave] = hi;
@@ -304,26 +357,40 @@ __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s,
     sh.hist[i] = 0;
     sh.fill[i] = 0;
   }
-  if (tid == 0) sh.max_bin = 0;
+  if (tid == 0) sh.crowded = 0;
   __syncthreads();
 #pragma unroll
   for (int w = 0; w < kSelectThreads / 64; ++w) {
-    lo = fmin(lo, sh.red_lo[w]);
-    hi = fmax(hi, sh.red_hi[w]);
+    lo = fminf(lo, sh.red_lo[w]);
+    hi = fmaxf(hi, sh.red_hi[w]);
   }
-  const double inv = (double)kBins / (hi - lo);
-  if (!(inv > 0.0) || !(inv < 1.0e300)) return false;        // all scores equal (or range overflow)
+  const float inv = (float)kBins / (hi - lo);
+  if (!(inv > 0.0f) || !(inv < 1.0e30f)) return false;       // all scores equal in single precision (or range overflow)
+  // rounding, subtraction of lo, multiplication by a positive constant and truncation are all monotone
   auto bin_of = [&](double x) {
-    int b = (int)((x - lo) * inv);
-    return b > kBins - 1 ? kBins - 1 : b;
+    const int b = (int)(((float)x - lo) * inv);
+    return (uint32_t)(b > kBins - 1 ? kBins - 1 : b);
   };
-  for_each([&](int64_t, double x) { atomicAdd(&sh.hist[bin_of(x)], 1u); });
+  // histogram; the count an atomic returns is the entry's arrival order inside its bucket, kept (with the bucket)
+  // for the scatter below so that the resident case needs no second pass of atomics
+  if (resident) {
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      bins[u] = 0;
+      if (tid + (int64_t)u * kSelectThreads < L) {
+        const uint32_t b = bin_of(sc[u]);
+        bins[u] = b | (atomicAdd(&sh.hist[b], 1u) << 11);
+      }
+    }
+  } else {
+    for (int64_t j = tid; j < L; j += kSelectThreads) atomicAdd(&sh.hist[bin_of(s[j])], 1u);
+  }
   __syncthreads();
   // thread t owns buckets kBins-1-2t and kBins-2-2t (descending): suffix counts by an inclusive scan
   const int b0 = kBins - 1 - 2 * tid, b1 = kBins - 2 - 2 * tid;
   const uint32_t c0 = sh.hist[b0], c1 = sh.hist[b1];
   uint32_t total;
-  const uint32_t incl = block_scan_incl(c0 + c1, sh, &total);
+  const uint32_t incl = block_scan_incl<true>(c0 + c1, sh, &total);
   const uint32_t excl = incl - (c0 + c1);
   sh.base[b0] = excl;
   sh.base[b1] = excl + c0;
@@ -335,29 +402,34 @@ __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s,
   __syncthreads();
   const uint32_t n_cand = sh.n_cand;
   const int t_bin = (int)sh.t_bin;
-  {
-    uint32_t mc = (b0 >= t_bin ? c0 : 0u);
-    mc = (b1 >= t_bin && c1 > mc) ? c1 : mc;
+  if ((int64_t)n_cand > cap) return false;
+  // a candidate bucket too crowded to rank by comparison: seen by every thread after the scatter's barrier
+  if ((b0 >= t_bin && c0 > kMaxBinRank) || (b1 >= t_bin && c1 > kMaxBinRank)) sh.crowded = 1;
+  // scatter the candidates into bucket-grouped order
+  auto put = [&](uint32_t pos, int64_t j, double x, uint32_t b) {
+    skeys[pos] = score_key(x);
+    sidx[pos] = (uint32_t)j;
+    sbin[pos] = (uint16_t)b;
+  };
+  if (resident) {
+    uint32_t pos[kPer];                                      // every bucket offset is fetched before the first store
 #pragma unroll
-    for (int m = 1; m < 64; m <<= 1) {
-      const uint32_t o = __shfl_xor(mc, m);
-      mc = o > mc ? o : mc;
+    for (int u = 0; u < kPer; ++u) pos[u] = sh.base[bins[u] & (uint32_t)(kBins - 1)] + (bins[u] >> 11);
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int64_t j = tid + (int64_t)u * kSelectThreads;
+      const uint32_t b = bins[u] & (uint32_t)(kBins - 1);
+      if (j < L && (int)b >= t_bin) put(pos[u], j, sc[u], b);
     }
-    if (lane == 0) atomicMax(&sh.max_bin, mc);
+  } else {
+    for (int64_t j = tid; j < L; j += kSelectThreads) {
+      const double x = s[j];
+      const uint32_t b = bin_of(x);
+      if ((int)b >= t_bin) put(sh.base[b] + atomicAdd(&sh.fill[b], 1u), j, x, b);
+    }
   }
   __syncthreads();
-  if ((int64_t)n_cand > cap || sh.max_bin > kMaxBinRank) return false;
-  // scatter the candidates into bucket-grouped order
-  for_each([&](int64_t j, double x) {
-    const int b = bin_of(x);
-    if (b >= t_bin) {
-      const uint32_t pos = sh.base[b] + atomicAdd(&sh.fill[b], 1u);
-      skeys[pos] = score_key(x);
-      sidx[pos] = (uint32_t)j;
-      sbin[pos] = (uint16_t)b;
-    }
-  });
-  __syncthreads();
+  if (sh.crowded) return false;
   // rank inside the bucket, write the index at its final position
   const int64_t out_base = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * l_p;
   for (uint32_t pos = tid; pos < n_cand; pos += kSelectThreads) {
@@ -400,12 +472,7 @@ __device__ __forceinline__ void radix_collect(const double* __restrict__ s, int6
         c4[q] = sh.hist[255 - 4 * lane - q];
         tot += c4[q];
       }
-      uint32_t incl = tot;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        const uint32_t o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-      }
+      const uint32_t incl = wave_scan_incl(tot);
       uint32_t excl = incl - tot;
       if (excl < need && need <= incl) {
 #pragma unroll
@@ -597,18 +664,26 @@ apbv_status launch_compress(const CompressParams& p_in, hipStream_t stream) {
     const apbv_status st = launch_matrix_scores(p, scores, ws + stats_off, stream);
     if (st != APBV_OK) return st;
   } else {
-    // pooled query
-    if (p.d == 128)
-      launch(pool_query_kernel<128>, dim3(p.hkv, p.batch), dim3(1024), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv);
+    // pooled query, as n_split partial sums
+    const int n_split = pool_splits(p.q_probe.tokens * p.group, (int64_t)p.batch * p.hkv);
+    const int64_t rows_per_split = (p.q_probe.tokens * p.group + n_split - 1) / n_split;
+    const bool wide = rows_per_split >= 4 * 1024 / (p.d / 8);
+    const dim3 pool_grid(n_split, p.hkv, p.batch);
+    if (p.d == 128 && wide)
+      launch(pool_query_kernel<128, 1024>, pool_grid, dim3(1024), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv, n_split);
+    else if (p.d == 128)
+      launch(pool_query_kernel<128, 256>, pool_grid, dim3(256), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv, n_split);
+    else if (wide)
+      launch(pool_query_kernel<64, 1024>, pool_grid, dim3(1024), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv, n_split);
     else
-      launch(pool_query_kernel<64>, dim3(p.hkv, p.batch), dim3(1024), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv);
+      launch(pool_query_kernel<64, 256>, pool_grid, dim3(256), 0, p.q_probe, p.q_probe.tokens, p.group, qbar, p.hkv, n_split);
     // scores: one outer iteration per workgroup: 4 rows in flight per thread, many small workgroups
     const int rows_per_block = 4 * 256 / (p.d / 8);
     dim3 grid((unsigned)((p.L + rows_per_block - 1) / rows_per_block), p.hkv, p.batch);
     if (p.d == 128)
-      launch(score_kernel<128>, grid, dim3(256), 0, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
+      launch(score_kernel<128>, grid, dim3(256), 0, p.k, p.L, qbar, n_split, scores, p.scores_out, p.hkv, rows_per_block);
     else
-      launch(score_kernel<64>, grid, dim3(256), 0, p.k, p.L, qbar, scores, p.scores_out, p.hkv, rows_per_block);
+      launch(score_kernel<64>, grid, dim3(256), 0, p.k, p.L, qbar, n_split, scores, p.scores_out, p.hkv, rows_per_block);
   }
   if (p.l_p > 0) {
     // select + order

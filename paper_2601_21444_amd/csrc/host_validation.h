@@ -141,9 +141,19 @@ inline size_t query_attention_workspace_bytes(int batch, int n_q_heads, int head
   return (size_t)ks.n_splits * (align256(rows * head_dim * 2) + align256(rows * sizeof(float)));
 }
 
-// ---- workspace of the compression call: [pooled query | scores | sort arrays of the exact fallback when they do
-// not fit the LDS]
+// ---- workspace of the compression call: [partial sums of the pooled query | scores | sort arrays of the exact
+// fallback when they do not fit the LDS]
 constexpr int64_t kLdsSortMax = 8192;          // entries that fit the LDS selection arrays (14 bytes each)
+constexpr int kPoolSplitMax = 8;               // workgroups (partial sums) per pooled query
+
+// Ranges the n_rows = n_q * G probe rows of one pooled query are cut into: about 64 rows each, but no more ranges
+// than it takes to give every compute unit two (n_pooled = batch * Hkv pooled queries share the 256 of them).
+inline int pool_splits(int64_t n_rows, int64_t n_pooled) {
+  int64_t s = (n_rows + 63) / 64;
+  const int64_t fill = 512 / (n_pooled < 1 ? 1 : n_pooled);
+  s = s > fill ? fill : s;
+  return (int)(s < 1 ? 1 : (s > kPoolSplitMax ? kPoolSplitMax : s));
+}
 
 inline int64_t pow2_ceil(int64_t x) {
   int64_t n = 1;
@@ -161,7 +171,7 @@ inline CompressWorkspace plan_compress_workspace(int batch, int hkv, int d, int6
   CompressWorkspace w;
   size_t off = 0;
   w.qbar_off = off;
-  off = align256(off + (size_t)batch * hkv * d * sizeof(double));
+  off = align256(off + (size_t)batch * hkv * kPoolSplitMax * d * sizeof(double));
   w.scores_off = off;
   off = align256(off + (size_t)batch * hkv * (size_t)L * sizeof(double));
   // capacity of the sort arrays: room for the candidates of the fast path (the winners plus the rest
