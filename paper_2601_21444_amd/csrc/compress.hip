@@ -187,7 +187,10 @@ __global__ __launch_bounds__(256) void score_kernel(View k, int64_t L, const dou
     const int u = (odd1 ? 2 : 0) + (odd2 ? 1 : 0);     // the row this lane ended up with
     const int64_t j = r0 + u * RPS + rsub;
     if (c >= LPR - 4 && j < r_end) {                   // the last quad of the row's lanes holds complete sums
-      s_ws[out_base + j] = acc;
+      // written through to memory as the kernel runs (device-scope store): left to the write-back cache, the
+      // scores of a large batch are flushed when the kernel ends, with nothing left to overlap the flush
+      __hip_atomic_store(reinterpret_cast<long long*>(s_ws + out_base + j), __double_as_longlong(acc), __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
       if (s_out) s_out[out_base + j] = acc;
     }
   }
@@ -405,28 +408,42 @@ __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s,
   if ((int64_t)n_cand > cap) return false;
   // a candidate bucket too crowded to rank by comparison: seen by every thread after the scatter's barrier
   if ((b0 >= t_bin && c0 > kMaxBinRank) || (b1 >= t_bin && c1 > kMaxBinRank)) sh.crowded = 1;
-  // scatter the candidates into bucket-grouped order
-  auto put = [&](uint32_t pos, int64_t j, double x, uint32_t b) {
-    skeys[pos] = score_key(x);
-    sidx[pos] = (uint32_t)j;
-    sbin[pos] = (uint16_t)b;
-  };
+  // scatter the candidates into bucket-grouped order.  Every wave walks all kPer iterations for the few lanes
+  // that hold a candidate, so the body is two stores (index, raw score); key and bucket follow below.
   if (resident) {
-    uint32_t pos[kPer];                                      // every bucket offset is fetched before the first store
-#pragma unroll
-    for (int u = 0; u < kPer; ++u) pos[u] = sh.base[bins[u] & (uint32_t)(kBins - 1)] + (bins[u] >> 11);
+    // Every bucket offset is fetched before the first store.  Lanes without a candidate all read one and the
+    // same word (a broadcast), so that only the few candidates' reads can collide on an LDS bank.
+    uint32_t pos[kPer];
 #pragma unroll
     for (int u = 0; u < kPer; ++u) {
-      const int64_t j = tid + (int64_t)u * kSelectThreads;
       const uint32_t b = bins[u] & (uint32_t)(kBins - 1);
-      if (j < L && (int)b >= t_bin) put(pos[u], j, sc[u], b);
+      pos[u] = sh.base[(int)b >= t_bin ? b : (uint32_t)(kBins - 1)] + (bins[u] >> 11);
+    }
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const uint32_t j = (uint32_t)tid + (uint32_t)u * kSelectThreads;
+      if (j < (uint32_t)L && (int)(bins[u] & (uint32_t)(kBins - 1)) >= t_bin) {
+        sidx[pos[u]] = j;
+        skeys[pos[u]] = (uint64_t)__double_as_longlong(sc[u]);
+      }
     }
   } else {
     for (int64_t j = tid; j < L; j += kSelectThreads) {
       const double x = s[j];
       const uint32_t b = bin_of(x);
-      if ((int)b >= t_bin) put(sh.base[b] + atomicAdd(&sh.fill[b], 1u), j, x, b);
+      if ((int)b >= t_bin) {
+        const uint32_t pos = sh.base[b] + atomicAdd(&sh.fill[b], 1u);
+        sidx[pos] = (uint32_t)j;
+        skeys[pos] = (uint64_t)__double_as_longlong(x);
+      }
     }
+  }
+  __syncthreads();
+  // the owner of a candidate position turns the raw score into its key and bucket, in place
+  for (uint32_t pos = tid; pos < n_cand; pos += kSelectThreads) {
+    const double x = __longlong_as_double((long long)skeys[pos]);
+    skeys[pos] = score_key(x);
+    sbin[pos] = (uint16_t)bin_of(x);
   }
   __syncthreads();
   if (sh.crowded) return false;
@@ -438,7 +455,19 @@ __device__ __forceinline__ bool bucket_rank_select(const double* __restrict__ s,
     const uint64_t key = skeys[pos];
     const uint32_t idx = sidx[pos];
     uint32_t rank = 0;
-    for (uint32_t q = first; q < first + cnt; ++q) rank += precedes(skeys[q], sidx[q], key, idx) ? 1u : 0u;
+    const uint32_t end = first + cnt;                        // cnt >= 1: the entry itself
+    for (uint32_t q = first; q < end; q += 4) {              // four entries' reads in flight
+      uint64_t kq[4];
+      uint32_t iq[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const uint32_t qq = q + e < end ? q + e : end - 1;
+        kq[e] = skeys[qq];
+        iq[e] = sidx[qq];
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) rank += (q + e < end && precedes(kq[e], iq[e], key, idx)) ? 1u : 0u;
+    }
     if (first + rank < (uint32_t)l_p) idx_out[out_base + first + rank] = (int32_t)idx;
   }
   return true;
