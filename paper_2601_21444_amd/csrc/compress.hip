@@ -8,10 +8,12 @@
 // agrees with a float64 evaluation (float32 accumulation flips near-equal neighbours).
 //
 // Four launches on the caller's stream:
-//   pool_query_kernel   q_bar (float64)                                   [Hkv x batch workgroups]
-//   score_kernel        s[v, j], 16-byte coalesced reads of K rows        [L/64 x Hkv x batch]
-//   select_kernel       radix select of the l_p-th largest key + bitonic sort of the winners into
-//                       (score descending, index ascending) order         [Hkv x batch]
+//   pool_query_kernel   partial sums of q_bar (float64), up to 8 row ranges per pooled query
+//                                                                         [splits x Hkv x batch workgroups]
+//   score_kernel        s[v, j], 16-byte coalesced reads of K rows; adds the partial sums of q_bar as it starts;
+//                       scores stored through to memory as it runs         [L/64 x Hkv x batch]
+//   select_kernel       bucket sort by value of the scores above the l_p-th largest (exact fallback: radix select
+//                       + bitonic sort), into (score descending, index ascending) order   [Hkv x batch]
 //   gather_kernel       K_c, V_c rows                                     [l_p*Hkv/.. x batch]
 #include <mutex>
 #include "apbv_common.h"
