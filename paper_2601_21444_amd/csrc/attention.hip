@@ -673,13 +673,27 @@ __device__ __forceinline__ void attention_workgroup(const AttnParams& p, const i
   }
 }
 
+// Work items are numbered heaviest first, `period` consecutive ones (the KV heads, batch items and key ranges of one
+// query tile) being equally heavy, and are dealt to the XCDs eight at a time.  Dealt always in the same direction,
+// XCD 0 would get the heaviest item of every row of eight and XCD 7 the lightest -- 4 to 12 % more work for the one
+// than for the other with a causal block.  Odd rows are therefore dealt in the opposite direction, in whole groups of
+// `period` XCDs where that divides eight, so that an XCD keeps serving the same KV head (its L2 holds that head's
+// K/V), item by item otherwise.
+__device__ __forceinline__ int deal(int row, int xcd, int period) {
+  if (row & 1) {
+    const int s = (period < kXcds && kXcds % period == 0) ? period : (period % kXcds == 0 ? kXcds : 1);
+    xcd = (kXcds / s - 1 - xcd / s) * s + xcd % s;
+  }
+  return row * kXcds + xcd;
+}
+
 // ---- workgroup -> (query tile, head, batch, key range); the heads of one KV group share an XCD
 template <int D, int W>
 __global__ __launch_bounds__(64 * W, 2) void host_attention_kernel(const AttnParams p, const int n_qtiles,
                                                                    const int n_items) {
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
-  const int item_split = (slot / p.group) * kXcds + xcd;
+  const int item_split = deal(slot / p.group, xcd, p.batch * p.hkv * p.n_splits);
   if (item_split >= n_items) return;
   const int split = item_split % p.n_splits;     // key ranges of one item share nothing: spread them over the XCDs
   const int item = item_split / p.n_splits;
@@ -699,7 +713,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void host_attention_group_kernel(co
   const int group = gp.item[0].group, hkv = gp.item[0].hkv;
   const int xcd = blockIdx.x % kXcds;
   const int slot = blockIdx.x / kXcds;
-  const int unit = (slot / group) * kXcds + xcd;
+  const int unit = deal(slot / group, xcd, hkv);
   if (unit >= gp.sched.n_entries * hkv) return;
   const int g = slot % group;
   const int entry = unit / hkv, kvh = unit % hkv;
