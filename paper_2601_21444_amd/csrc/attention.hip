@@ -720,7 +720,10 @@ __global__ __launch_bounds__(64 * kWaves, 2) void host_attention_group_kernel(co
   int m, qt;
   decode_group_entry(gp.sched, entry, m, qt);
   if (m >= gp.n_items || qt < 0 || (int64_t)qt * kBM >= gp.item[m].L) return;      // never taken for a schedule the launcher built
-  attention_workgroup<D, kWaves>(gp.item[m], qt, 0, kvh, g, 0);
+  // (a copy, so that the fields live in scalar registers like the single-problem kernel's by-value argument
+  // instead of being fetched from the argument block where they are used)
+  const AttnParams item = gp.item[m];
+  attention_workgroup<D, kWaves>(item, qt, 0, kvh, g, 0);
 }
 
 }  // namespace
