@@ -108,6 +108,40 @@ def test_random_shapes_compress_bit_exact(seed):
     np.testing.assert_array_equal(bits_of(v_c), vc_r)
 
 
+@pytest.mark.parametrize("d,hkv,group,n_q", [(128, 2, 8, 64), (64, 4, 2, 130), (128, 1, 3, 5)])
+def test_compress_is_the_same_at_every_batch_size(d, hkv, group, n_q):
+    """The pooled query is summed over a number of row ranges that depends on the batch size (few pooled queries:
+    up to eight workgroups each; many: one or two, 1024 threads wide).  The addends are bf16 and the sums fp64, so
+    with ordinary data every partition gives the same bits: an item must get identical scores and indices alone and
+    inside batches of 3, 40 and 300, and every item of a batch must match the oracle."""
+    rng = np.random.default_rng((73, d, hkv))
+    hq, L, l_p = hkv * group, 2100, 300
+    items = 4                                                   # distinct items, repeated to fill the larger batches
+    qp = rand_bits(rng, (items, n_q, hq, d))
+    k = rand_bits(rng, (items, L, hkv, d))
+    v = rand_bits(rng, (items, L, hkv, d))
+    ref = [oracle.compress_kv(qp[i], k[i], v[i], l_p) for i in range(items)]
+    singles = []
+    for i in range(items):
+        idx, _, _, sc = apbv.apbv_compress_kv(dev(qp[i]), dev(k[i]), dev(v[i]), l_p, return_scores=True)
+        np.testing.assert_array_equal(idx.cpu().numpy(), ref[i][0])
+        singles.append((idx.cpu().numpy(), sc.cpu().numpy()))
+    for batch in (3, 40, 300):
+        pick = np.arange(batch) % items
+        print(f"batch invariance: d={d} hkv={hkv} group={group} n_q={n_q} batch={batch}", flush=True)
+        idx, k_c, v_c, sc = apbv.apbv_compress_kv(dev(qp[pick]), dev(k[pick]), dev(v[pick]), l_p, return_scores=True)
+        torch.cuda.synchronize()
+        idx, sc = idx.cpu().numpy(), sc.cpu().numpy()
+        bits_of = lambda t: t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        k_c, v_c = bits_of(k_c), bits_of(v_c)
+        for b in range(batch):
+            i = int(pick[b])
+            assert np.array_equal(sc[b].view(np.uint64), singles[i][1].view(np.uint64)), f"scores of item {b} differ from the single call"
+            np.testing.assert_array_equal(idx[b], singles[i][0])
+            np.testing.assert_array_equal(k_c[b], ref[i][1])
+            np.testing.assert_array_equal(v_c[b], ref[i][2])
+
+
 @pytest.mark.parametrize("gain", [8.0, 40.0])
 def test_attention_with_peaked_logits(gain):
     """Queries scaled up so that the softmax is nearly one-hot and the running maximum jumps by far more than the
