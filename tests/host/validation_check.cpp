@@ -1,6 +1,7 @@
 // Host check of the C ABI's argument validation and planning (csrc/host_validation.h), compiled with the plain C++
 // compiler under -fsanitize=address,undefined: every rejection case returns its status without touching the forged
 // pointers, and the planners stay in range over a sweep of shapes.
+#include <initializer_list>
 #include <cstdio>
 #include <cstdlib>
 #include <limits>
@@ -122,6 +123,18 @@ int main() {
       EXPECT(w1.n_sort >= l_p && (w1.n_sort & (w1.n_sort - 1)) == 0 && w3.total >= w1.total);
       EXPECT(compress_workspace_bytes_checked(1, 2, 128, L, l_p) == w1.total);
     }
+  // pooled-query partition: about 64 probe rows per range, at most kPoolSplitMax, no more ranges than fill the chip
+  // twice over; and the partial sums of every partition fit the region the workspace plan reserves for them
+  EXPECT(pool_splits(512, 2) == 8 && pool_splits(512, 192) == 2 && pool_splits(512, 1000) == 1 && pool_splits(10, 1) == 1);
+  EXPECT(pool_splits(100000, 1) == kPoolSplitMax && pool_splits(1, 1) == 1 && pool_splits(130, 4) == 3);
+  for (int batch : {1, 2, 7, 96, 300})
+    for (int hkv : {1, 2, 4, 8})
+      for (int64_t rows : {1, 63, 64, 65, 512, 4096}) {
+        const int n = pool_splits(rows, (int64_t)batch * hkv);
+        EXPECT(n >= 1 && n <= kPoolSplitMax);
+        const CompressWorkspace w = plan_compress_workspace(batch, hkv, 128, 1024, 16);
+        EXPECT(w.qbar_off + (size_t)batch * hkv * n * 128 * sizeof(double) <= w.scores_off);
+      }
   EXPECT(compress_workspace_bytes_checked(1, 2, 128, 0, 0) == 0 && compress_workspace_bytes_checked(1, 2, 128, 8, 9) == 0);
   EXPECT(compress_workspace_bytes_checked(0, 2, 128, 8, 1) == 0 && compress_workspace_bytes_checked(1, 2, 100, 8, 1) == 0);
   if (failures) return 1;
