@@ -65,6 +65,8 @@ def parse_args():
     ap.add_argument("--no-extras", action="store_true", help="skip the short timings of the query-block, physical-host "
                     "and alternative-reduction entry points")
     ap.add_argument("--no-per-config", action="store_true", help="skip the short timings of the other configurations")
+    ap.add_argument("--reducer-batch", type=int, default=0,
+                    help="also time the whole compression call under each score reduction at this batch (0: skip)")
     ap.add_argument("--compress-batch", type=int, default=96,
                     help="batch of the HBM-bound compression measurement (working set far beyond the 256 MB cache)")
     return ap.parse_args()
@@ -218,6 +220,8 @@ def main():
         result["per_config"] = per_config(apbv, torch, np, wl, name, result)
     if not args.no_extras:
         result["extras"] = extras(apbv, torch, cfg, q_probe, q, k_a, v_a, k_p, v_p, k, v, scale)
+    if args.reducer_batch > 0:
+        result["reducers_batched"] = reducers_batched(apbv, torch, cfg, q_probe, k, v, scale, args.reducer_batch)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(np, x, cfg, scale, args.cpu_rows)
     print(json.dumps(result), flush=True)
@@ -356,6 +360,24 @@ def extras(apbv, torch, cfg, q_probe, q, k_a, v_a, k_p, v_p, k, v, scale):
                                                         workspace=rws, idx_out=idx, k_c_out=k_c, v_c_out=v_c), iters=20)
         red[name] = round(ms * 1e3, 1)
     out["compress_us_by_reducer"] = red
+    return out
+
+
+def reducers_batched(apbv, torch, cfg, q_probe, k, v, scale, batch):
+    """The whole compression call under each reduction of the score matrix at a batch that fills the chip (the block
+    repeated; timing only).  The matrix reductions form n_q*G x L logits per KV head on the matrix cores."""
+    hq, hkv, d = cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    qp, kb, vb = (t.unsqueeze(0).repeat(batch, 1, 1, 1) for t in (q_probe, k, v))
+    idx = torch.empty((batch, hkv, cfg.l_p), dtype=torch.int32, device="cuda")
+    k_c = torch.empty((batch, cfg.l_p, hkv, d), dtype=torch.bfloat16, device="cuda")
+    v_c = torch.empty_like(k_c)
+    out = {"batch": batch, "logit_flops_per_call": 2.0 * batch * hq * cfg.n_q * cfg.L * d}
+    for name in ("sum", "max", "softmax_sum"):
+        nbytes = apbv.apbv_compress_reduced_workspace_bytes(name, batch, hq, hkv, d, cfg.n_q, cfg.L, cfg.l_p)
+        rws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+        ms = timed(torch, lambda: apbv.apbv_compress_kv(qp, kb, vb, cfg.l_p, reducer=name, softmax_scale=scale,
+                                                        workspace=rws, idx_out=idx, k_c_out=k_c, v_c_out=v_c), iters=20, warmup=5)
+        out[name + "_us"] = round(ms * 1e3, 1)
     return out
 
 
