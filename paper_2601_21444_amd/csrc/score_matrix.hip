@@ -25,7 +25,9 @@
 namespace apbv {
 namespace {
 
-constexpr int kChunkKeys = 256;        // keys per partial row statistic
+constexpr int kChunkKeys = 256;        // smallest number of keys per partial row statistic (sizes the workspace)
+constexpr int kMaxChunkKeys = 4096;    // largest
+constexpr int64_t kStatsMinWorkgroups = 2 * 768;   // keep at least two rounds of workgroups in the statistics launch
 constexpr int kMaxStatRows = 8192;     // rows whose statistics fit the LDS of the kMass pass (4 bytes each)
 constexpr int kResident = 256;         // resident vectors per workgroup (64 per wave)
 
@@ -53,6 +55,7 @@ struct RowsParams {
   int n_rows;          // R = n_q * G
   int r_pad;           // R rounded up to a multiple of 32
   int group, hkv, n_chunks;
+  int chunk_keys;      // keys per partial row statistic: a multiple of kChunkKeys
   float scale_log2;    // softmax_scale * log2(e)
   float2* partial;     // [batch, Hkv, n_chunks, r_pad]  (maximum of the scaled logits in the log2 domain, sum of exp2)
   float* stats;        // [batch, Hkv, r_pad]            c_r = maximum + log2(normaliser); +inf for padding rows
@@ -151,8 +154,8 @@ __global__ __launch_bounds__(256, 3) void matrix_reduce_kernel(const RowsParams 
     const int n_rg = (p.r_pad + kResident - 1) / kResident;
     res0 = (int64_t)(blockIdx.x % n_rg) * kResident;
     ch = blockIdx.x / n_rg;
-    str0 = (int64_t)ch * kChunkKeys;
-    str_end = str0 + kChunkKeys < p.L ? str0 + kChunkKeys : p.L;
+    str0 = (int64_t)ch * p.chunk_keys;
+    str_end = str0 + p.chunk_keys < p.L ? str0 + p.chunk_keys : p.L;
   }
   auto resident_row = [&](int64_t i) { return kKeysResident ? key_row(p, b, v, i) : probe_row(p, b, v, (int)i); };
 
@@ -398,7 +401,18 @@ apbv_status launch_matrix_scores(const CompressParams& cp, double* scores, void*
   p.r_pad = (int)((n_rows + 31) / 32 * 32);
   p.group = cp.group;
   p.hkv = cp.hkv;
-  p.n_chunks = (int)((cp.L + kChunkKeys - 1) / kChunkKeys);
+  // Keys per workgroup of the statistics pass.  A workgroup loads 256 resident probe rows (64 KB) before it streams
+  // its keys, so a chunk of 256 keys spends as long on the prologue as on the matrix work; chunks grow while the
+  // launch still has two workgroups for every slot of the chip (three workgroups per compute unit).  (Batch 16 at
+  // 512 x 16384 logits per head: 512-key chunks, 102 -> 93 us, and the combine kernel 10 -> 6 us.)
+  int chunk = kChunkKeys;
+  {
+    const int64_t n_rg = ((n_rows + 31) / 32 * 32 + kResident - 1) / kResident;
+    auto n_wg_at = [&](int c) { return n_rg * ((cp.L + c - 1) / c) * cp.hkv * cp.batch; };
+    while (chunk < kMaxChunkKeys && n_wg_at(2 * chunk) >= kStatsMinWorkgroups) chunk *= 2;
+  }
+  p.chunk_keys = chunk;
+  p.n_chunks = (int)((cp.L + chunk - 1) / chunk);
   p.scale_log2 = cp.scale_log2;
   p.partial = nullptr;
   p.stats = nullptr;

@@ -141,3 +141,28 @@ def test_reduced_compress_batched_strided():
             for h in range(hkv):
                 check_selection(idx[b, h].cpu().numpy(), s_ref[h], s[b, h].cpu().numpy(), l_p, tol)
                 np.testing.assert_array_equal(host_bits(k_c[b])[:, h], k[b][idx[b, h].cpu().numpy(), h])
+
+
+def test_softmax_mass_with_larger_statistics_chunks():
+    """A large batch makes the statistics pass take more keys per workgroup (512 to 4096 instead of 256, a ragged last
+    chunk included): every item of the batch must still match the oracle of its own data."""
+    rng = np.random.default_rng(54)
+    items, B, hq, hkv, d, n_q, L, l_p = 3, 200, 4, 2, 128, 30, 2500, 64       # 60 rows per head: one row group
+    scale = 1.0 / math.sqrt(d)
+    qp = rand_bits(rng, (items, n_q, hq, d))
+    k, v = rand_bits(rng, (items, L, hkv, d)), rand_bits(rng, (items, L, hkv, d))
+    pick = np.arange(B) % items
+    idx, k_c, v_c, s = apbv.apbv_compress_kv(dev(qp[pick]), dev(k[pick]), dev(v[pick]), l_p, reducer="softmax_sum",
+                                             softmax_scale=scale, return_scores=True)
+    torch.cuda.synchronize()
+    idx, s, k_c = idx.cpu().numpy(), s.cpu().numpy(), host_bits(k_c)
+    refs = [oracle.importance_scores_softmax_sum(qp[i], k[i], scale) for i in range(items)]
+    for b in range(B):
+        i = int(pick[b])
+        tol = TOL_MASS * np.abs(refs[i]).max()
+        assert np.abs(s[b] - refs[i]).max() <= tol, f"item {b}"
+        np.testing.assert_allclose(s[b].sum(axis=1), n_q * (hq // hkv), rtol=1e-4)
+        if b < 2 * items or b >= B - items:              # the full selection check on the first and last items
+            for h in range(hkv):
+                check_selection(idx[b, h], refs[i][h], s[b, h], l_p, tol)
+                np.testing.assert_array_equal(k_c[b][:, h], k[i][idx[b, h], h])
