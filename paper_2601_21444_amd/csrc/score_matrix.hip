@@ -10,7 +10,7 @@
 //
 // One kernel template does all the matrix work.  A workgroup of four waves keeps 256 "resident" vectors in
 // registers as MFMA B operands (64 per wave) and streams the other side through LDS in tiles of 32 vectors
-// (A operand, double buffered, shared by the four waves).  Each 32x32 accumulator then has the streamed
+// (A operand, a ring of four tiles filled by LDS-direct loads, shared by the four waves).  Each 32x32 accumulator then has the streamed
 // vectors along its register axis and one resident vector per lane, so every reduction over the streamed side
 // is per lane, plus one exchange between the two lane halves at the end:
 //
@@ -35,6 +35,16 @@ enum Mode { kMax = 1, kMass = 2, kStats = 3 };
 
 __device__ __forceinline__ f32x16 mfma(const bf16x8 a, const bf16x8 b, const f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// LDS-direct 16-byte load: lane l's bytes land at lds_dst + 16*l (lds_dst wave-uniform, in M0, which addresses the
+// first 64 KB of the workgroup's LDS).  Issued through inline assembly: the kernel orders these loads against the LDS
+// reads itself (s_waitcnt vmcnt(0) + barrier), the compiler's wait-count insertion does not know about them.
+__device__ __forceinline__ void dma16_lane(const void* addr, uint32_t lds_dst) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_dst), "v"(addr) : "memory", "m0");
+}
+__device__ __forceinline__ uint32_t lds_addr(const unsigned char* p) {
+  return (uint32_t)(size_t)(__attribute__((address_space(3))) const unsigned char*)p;
 }
 
 // accumulator register i of lane half hh holds matrix row 8*(i/4) + 4*hh + i%4 (column = lane % 32)
@@ -133,8 +143,11 @@ __global__ __launch_bounds__(256, 3) void matrix_reduce_kernel(const RowsParams 
   constexpr int ROW_BYTES = D * 2;
   constexpr int TR = 32;                     // streamed vectors per LDS tile (64: no faster, twice the LDS)
   constexpr int PASSES = TR * KC / 256;      // 16-byte loads per thread per streamed tile
+  constexpr int RPW = 1024 / ROW_BYTES;      // tile rows one wave-wide LDS-direct load covers
+  constexpr int kTiles = 4;                  // streamed tiles resident in LDS
   constexpr bool kKeysResident = MODE != kStats;
-  __shared__ __attribute__((aligned(16))) unsigned char tile[2][TR * ROW_BYTES];
+  __shared__ __attribute__((aligned(1024))) unsigned char tile[kTiles][TR * ROW_BYTES];
+  static_assert(kTiles * TR * ROW_BYTES <= 65536 && PASSES * 4 * RPW == TR, "tile ring below 64 KB; four waves fill a tile");
   extern __shared__ float c_lds[];           // kMass: r_pad entries
 
   const int v = blockIdx.y, b = blockIdx.z;
@@ -173,23 +186,26 @@ __global__ __launch_bounds__(256, 3) void matrix_reduce_kernel(const RowsParams 
     for (int i = tid; i < p.r_pad; i += 256) c_lds[i] = st[i];
   }
 
-  // ---- streamed tiles: thread tid moves chunk tid % KC of tile rows (u*256 + tid) / KC
+  // ---- streamed tiles, global -> LDS without a stop in registers.  Wave-wide load (u, wave) fills the RPW tile rows
+  // from (4*u + wave) * RPW; lane l brings the 16-byte chunk that belongs at position l % KC of row l / KC of those,
+  // i.e. chunk (l % KC) ^ swz(row) of the vector (the swizzle is applied on the global side).
   typename CursorOf<!kKeysResident>::type cur[PASSES];
 #pragma unroll
-  for (int u = 0; u < PASSES; ++u) cur[u].init(p, b, v, str0 + (u * 256 + tid) / KC, 8 * (tid % KC), TR);
-  auto fetch = [&](u32x4 (&pre)[PASSES]) {           // loads the cursors' tile and moves them to the next one
+  for (int u = 0; u < PASSES; ++u) {
+    const int row = (4 * u + wave) * RPW + lane / KC;
+    cur[u].init(p, b, v, str0 + row, 8 * ((lane % KC) ^ swz(row)), TR);
+  }
+  const uint32_t tile_lds = lds_addr(tile[0]) + (uint32_t)(__builtin_amdgcn_readfirstlane(wave) * RPW * ROW_BYTES);
+  auto issue = [&](int slot) {                       // requests the cursors' tile into a ring slot, moves them on
 #pragma unroll
     for (int u = 0; u < PASSES; ++u) {
-      pre[u] = *reinterpret_cast<const u32x4*>(cur[u].get(p));
+      dma16_lane(cur[u].get(p), tile_lds + (uint32_t)(slot * TR * ROW_BYTES + 4 * u * RPW * ROW_BYTES));
       cur[u].advance(p);
     }
   };
-  auto stash = [&](const u32x4 (&pre)[PASSES], int buf) {
-#pragma unroll
-    for (int u = 0; u < PASSES; ++u) {
-      const int row = (u * 256 + tid) / KC;
-      *reinterpret_cast<u32x4*>(&tile[buf][row * ROW_BYTES + 16 * ((tid % KC) ^ swz(row))]) = pre[u];
-    }
+  auto arrive = [&]() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's share of the requested tiles has landed
+    __syncthreads();                                  // ... everyone's has, and everyone is done with the slots reloaded next
   };
 
   float red[2], z_run[2];
@@ -272,43 +288,21 @@ __global__ __launch_bounds__(256, 3) void matrix_reduce_kernel(const RowsParams 
     }
   };
 
-  // Tiles travel global -> registers -> LDS two tiles ahead of the MFMAs: while tile t is computed, tile t+1 is
-  // in registers on its way to the other LDS buffer and the loads of tile t+2 are in flight (one tile ahead
-  // leaves only one tile's compute time to cover the L2 latency, and the barrier makes every wave wait for the
-  // slowest load).  Two register sets alternate, so the loop is written out for an even and an odd tile.
-  // (The statistics pass keeps more values live; with two register sets it spills at three waves per SIMD, so it
-  // prefetches one tile ahead only.)
-  constexpr bool kTwoAhead = MODE != kStats;
-  u32x4 pa[PASSES], pb[kTwoAhead ? PASSES : 1];
-  fetch(pa);
-  stash(pa, 0);
-  // everything loaded so far (the resident operands, the first tile) has arrived: vmcnt 0, said with the builtin
-  // so that the compiler's own wait-count bookkeeping knows it
+  // Tile t lives in ring slot t % 4.  One barrier per two tiles: after the barrier in front of tiles t, t+1 both have
+  // landed and everyone is done with tiles t-2, t-1, whose slots take the loads of tiles t+2, t+3.
+  // Everything loaded so far with ordinary loads (the resident operands) has arrived: vmcnt 0, said with the builtin
+  // so that the compiler's own wait-count bookkeeping knows it; from here on only tile loads are outstanding.
   __builtin_amdgcn_s_waitcnt(0x0F70);
-  if constexpr (kTwoAhead) {
-    if (str0 + TR < str_end) fetch(pa);
-    __syncthreads();
-    for (int64_t tile0 = str0; tile0 < str_end; tile0 += 2 * TR) {
-      if (tile0 + 2 * TR < str_end) fetch(pb);
-      compute(tile0, 0);
-      if (tile0 + TR >= str_end) break;
-      stash(pa, 1);
-      __syncthreads();
-      if (tile0 + 3 * TR < str_end) fetch(pa);
-      compute(tile0 + TR, 1);
-      if (tile0 + 2 * TR < str_end) stash(pb, 0);
-      __syncthreads();
-    }
-  } else {
-    __syncthreads();
-    int buf = 0;
-    for (int64_t tile0 = str0; tile0 < str_end; tile0 += TR, buf ^= 1) {
-      const bool more = tile0 + TR < str_end;
-      if (more) fetch(pa);
-      compute(tile0, buf);
-      if (more) stash(pa, buf ^ 1);
-      __syncthreads();
-    }
+  issue(0);
+  if (str0 + TR < str_end) issue(1);
+  arrive();
+  int slot = 0;
+  for (int64_t tile0 = str0; tile0 < str_end; tile0 += 2 * TR, slot ^= 2) {
+    if (tile0 + 2 * TR < str_end) issue(slot ^ 2);
+    if (tile0 + 3 * TR < str_end) issue((slot ^ 2) + 1);
+    compute(tile0, slot);
+    if (tile0 + TR < str_end) compute(tile0 + TR, slot + 1);
+    arrive();
   }
 
   // ---- the two lane halves hold disjoint streamed vectors for the same resident vector
