@@ -79,6 +79,30 @@ def test_random_shapes_all_attention_entry_points(seed):
         check(to_f64(res[1]), ref2, "group, second problem")
 
 
+@pytest.mark.parametrize("batch,hkv,group", [(4, 2, 2), (3, 2, 4), (5, 1, 3), (8, 2, 1), (2, 4, 7), (1, 8, 2), (9, 3, 2)])
+def test_attention_every_way_of_dealing_items_to_the_xcds(batch, hkv, group):
+    """Work items are dealt to the eight XCDs in rows of eight, odd rows in the opposite direction in groups of
+    batch * Hkv XCDs where that divides eight, item by item otherwise, unchanged where it is a multiple of eight:
+    every (batch, Hkv) class of that rule, over several query tiles, every item against the oracle, and the key-split
+    launch (whose item count is multiplied by the number of key ranges) against the unsplit one."""
+    rng = np.random.default_rng((74, batch, hkv, group))
+    d, L, l_a, n_p = 64, 700, 96, 160                      # three 256-row query tiles per head
+    hq = hkv * group
+    scale = 1.0 / math.sqrt(d)
+    q = rand_bits(rng, (batch, L, hq, d))
+    ka, va, kp, vp, kl, vl = (rand_bits(rng, (batch, n, hkv, d)) for n in (l_a, l_a, n_p, n_p, L, L))
+    args = [dev(x) for x in (q, ka, va, kp, vp, kl, vl)]
+    print(f"dealing: batch={batch} hkv={hkv} group={group}", flush=True)
+    out, lse = apbv.apbv_host_attention(*args, scale, return_lse=True)
+    out_s = apbv.apbv_query_attention(*args, scale, n_splits=3)
+    torch.cuda.synchronize()
+    for b in range(batch):
+        ref, lse_r = oracle.host_attention(q[b], ka[b], va[b], kp[b], vp[b], kl[b], vl[b], scale)
+        check(to_f64(out[b]), ref, f"item {b}")
+        check(to_f64(out_s[b]), ref, f"item {b}, key split")
+        np.testing.assert_allclose(lse[b].cpu().numpy().astype(np.float64), lse_r, atol=2e-3, rtol=0)
+
+
 @pytest.mark.parametrize("seed", range(10))
 def test_random_shapes_compress_bit_exact(seed):
     """Seeded random shapes through apbv_compress_kv: ragged block lengths around the kernels' row groupings, every
