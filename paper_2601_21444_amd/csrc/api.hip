@@ -101,7 +101,7 @@ const char* apbv_status_string(apbv_status s) {
   return "unknown apbv_status";
 }
 
-int apbv_version(void) { return 211; }
+int apbv_version(void) { return 212; }
 
 size_t apbv_compress_workspace_bytes(int batch, int n_kv_heads, int head_dim, int64_t L, int64_t l_p) {
   return compress_workspace_bytes_checked(batch, n_kv_heads, head_dim, L, l_p);
