@@ -45,6 +45,11 @@ GROUPS = [
     (8, 2, 64, [(257, 10, 1000), (1, 0, 0), (513, 0, 255), (256, 256, 0)]),
     (2, 1, 128, [(100, 5, 5)]),                                             # a group of one
     (2, 2, 128, [(64 + 37 * m, 16 * m, 300 * (7 - m)) for m in range(8)]),  # the maximum of eight problems
+    # KV head counts that divide eight, do not divide it, equal it (the three ways entries are dealt to the XCDs),
+    # each over enough query tiles for several rows of eight entries
+    (6, 3, 64, [(900, 64, 0), (1300, 64, 200)]),
+    (8, 4, 64, [(1100, 0, 100), (600, 32, 0), (300, 0, 0)]),
+    (8, 8, 64, [(800, 16, 16), (520, 0, 0)]),
 ]
 
 
