@@ -79,6 +79,38 @@ def test_random_shapes_all_attention_entry_points(seed):
         check(to_f64(res[1]), ref2, "group, second problem")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_mid_size_shapes_through_the_pipelined_rounds(seed):
+    """Blocks of several query tiles whose key loops run tens of four-tile rounds: segment boundaries that fall inside
+    a round, inside a tile, or exactly between rounds (every fifth case is aligned throughout), both head dimensions,
+    group sizes 1 / 2 / 7; plain, key-split and grouped launches."""
+    rng = np.random.default_rng((75, seed))
+    d = int(rng.choice([64, 128]))
+    hkv = int(rng.choice([1, 2, 3, 4]))
+    hq = hkv * int(rng.choice([1, 2, 7]))
+    L = int(rng.integers(600, 3000))
+    l_a = int(rng.choice([0, 32, 100, 1024, 2047, 2048, 1500]))
+    n_p = int(rng.choice([0, 96, 512, 1000, 3072, 3583]))
+    if seed % 5 == 0:
+        L, l_a, n_p = (L // 256) * 256, (l_a // 128) * 128, (n_p // 128) * 128
+    scale = 1.0 / math.sqrt(d)
+    q = rand_bits(rng, (L, hq, d))
+    ka, va, kp, vp, kl, vl = (rand_bits(rng, (n, hkv, d)) for n in (l_a, l_a, n_p, n_p, L, L))
+    print(f"mid-size shape seed={seed}: hq={hq} hkv={hkv} d={d} L={L} l_a={l_a} n_p={n_p}", flush=True)
+    ref, lse_r = oracle.host_attention(q, ka, va, kp, vp, kl, vl, scale)
+    args = [dev(x) for x in (q, ka, va, kp, vp, kl, vl)]
+    out, lse = apbv.apbv_host_attention(*args, scale, return_lse=True)
+    out_s, lse_s = apbv.apbv_query_attention(*args, scale, n_splits=int(rng.choice([2, 5, 9])), return_lse=True)
+    res = apbv.apbv_host_attention_group([tuple(args), tuple(args)], scale)
+    torch.cuda.synchronize()
+    check(to_f64(out), ref, "host_attention")
+    np.testing.assert_allclose(lse.cpu().numpy().astype(np.float64), lse_r, atol=2e-3, rtol=0)
+    check(to_f64(out_s), ref, "query_attention")
+    np.testing.assert_allclose(lse_s.cpu().numpy().astype(np.float64), lse_r, atol=2e-3, rtol=0)
+    assert torch.equal(res[0].view(torch.int16), out.view(torch.int16))
+    assert torch.equal(res[1].view(torch.int16), out.view(torch.int16))
+
+
 @pytest.mark.parametrize("batch,hkv,group", [(4, 2, 2), (3, 2, 4), (5, 1, 3), (8, 2, 1), (2, 4, 7), (1, 8, 2), (9, 3, 2)])
 def test_attention_every_way_of_dealing_items_to_the_xcds(batch, hkv, group):
     """Work items are dealt to the eight XCDs in rows of eight, odd rows in the opposite direction in groups of
